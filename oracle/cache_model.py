@@ -58,13 +58,16 @@ class CacheModel:
 
     # ---- Alg. 1 lines 4-6 + Alg. 2 ---------------------------------------------------------------
     def filter_cached(self, layer, experts):
-        """Alg. 1: drop predicted experts that are already in Q_cache (order kept, duplicates dropped)."""
+        """Alg. 1: drop predicted experts that are already in Q_cache (order kept, duplicates dropped).
+        The cached ones are touched, so the task built from the rest cannot pick them as victims."""
         seen, out = set(), []
         for e in experts:
             if e in seen:
                 continue
             seen.add(e)
-            if e not in self.queue[layer]:
+            if e in self.queue[layer]:
+                self._touch(layer, e)
+            else:
                 out.append(e)
         return out
 

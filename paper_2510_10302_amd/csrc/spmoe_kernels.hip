@@ -1,0 +1,656 @@
+// HIP kernels of the SP-MoE verify-layer hot path for gfx950 (CDNA4, wave64).
+//
+//   gate_topk_kernel     gate logits + softmax + top-k + gating scores (Eq. 1's G(x); Alg. 1's
+//                        Gates[l](s) and TopK_Index), one workgroup per token; the last workgroup to
+//                        finish groups the assignments by expert (counts / offsets / perm).
+//   expert_gemm_kernel   the grouped SwiGLU expert FFN (Eq. 1's E_i(x)) as two skinny GEMMs whose A
+//                        operand is the streamed weight tile and whose B operand is the (<= 16) token
+//                        tile held in registers; bf16 x bf16 -> fp32 on v_mfma_f32_16x16x32_bf16.
+//   expert_gemm_f32_kernel  the same contraction for fp32 weights on the vector ALU.
+//   combine_kernel       out[t] = sum_r w[t][r] * y[t][r] (+ shared experts), fixed summation order.
+//
+// The expert GEMMs are bound by streaming each active expert's weights from HBM exactly once: with a
+// handful of tokens per expert every weight byte feeds one MFMA.  Weights are therefore stored
+// pre-tiled (see spmoe_internal.h) so that one wave-wide 16-byte-per-lane load is a contiguous 1 KiB
+// line group that is already in MFMA A-operand order; no LDS staging of weights is needed.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <math.h>
+
+#include "spmoe_internal.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+// ---------------------------------------------------------------------------------------------
+// wave-level helpers (DPP within rows of 16 lanes, readlane across the four rows)
+// ---------------------------------------------------------------------------------------------
+#define DPP_QUAD_SWAP1 0xB1      // quad_perm [1,0,3,2]
+#define DPP_QUAD_SWAP2 0x4E      // quad_perm [2,3,0,1]
+#define DPP_ROW_HALF_MIRROR 0x141
+#define DPP_ROW_MIRROR 0x140
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov_f(float v) {
+    int i = __builtin_bit_cast(int, v);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(i, i, CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov_i(int v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ float readlane_f(float v, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+// Sum over the 64 lanes; every lane gets the same value, the order of additions is fixed.
+__device__ __forceinline__ float wave_sum(float v) {
+    v += dpp_mov_f<DPP_QUAD_SWAP1>(v);
+    v += dpp_mov_f<DPP_QUAD_SWAP2>(v);
+    v += dpp_mov_f<DPP_ROW_HALF_MIRROR>(v);
+    v += dpp_mov_f<DPP_ROW_MIRROR>(v);
+    return (readlane_f(v, 0) + readlane_f(v, 16)) + (readlane_f(v, 32) + readlane_f(v, 48));
+}
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_mov_f<DPP_QUAD_SWAP1>(v));
+    v = fmaxf(v, dpp_mov_f<DPP_QUAD_SWAP2>(v));
+    v = fmaxf(v, dpp_mov_f<DPP_ROW_HALF_MIRROR>(v));
+    v = fmaxf(v, dpp_mov_f<DPP_ROW_MIRROR>(v));
+    return fmaxf(fmaxf(readlane_f(v, 0), readlane_f(v, 16)), fmaxf(readlane_f(v, 32), readlane_f(v, 48)));
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+    v = min(v, dpp_mov_i<DPP_QUAD_SWAP1>(v));
+    v = min(v, dpp_mov_i<DPP_QUAD_SWAP2>(v));
+    v = min(v, dpp_mov_i<DPP_ROW_HALF_MIRROR>(v));
+    v = min(v, dpp_mov_i<DPP_ROW_MIRROR>(v));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __builtin_bit_cast(float, bits16 << 16); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Token -> expert grouping of T*k routed assignments (+ n_shared*T shared-expert assignments).
+// Runs inside one workgroup of 256 threads; s_idx / s_cnt / s_scan are workgroup LDS arrays.
+//   counts[e], offsets[e] (exclusive prefix, E_tot + 1 entries), perm = assignment ids a = t*k + r
+//   expert by expert, ascending inside an expert (a stable counting sort).  Shared expert s owns the
+//   assignments T*k + s*T + t, t = 0..T-1.
+// ---------------------------------------------------------------------------------------------
+#define GROUP_MAX_A (SPMOE_MAX_TOKENS * SPMOE_MAX_TOPK)   // 256 routed assignments at most
+
+__device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n_shared, int32_t* counts,
+                                  int32_t* offsets, int32_t* perm, int* s_idx, int* s_cnt, int* s_scan) {
+    const int tid = threadIdx.x;
+    const int A = T * k;
+    const int E_tot = E + n_shared;
+    for (int e = tid; e < 2 * 256; e += 256) s_cnt[e] = 0;
+    __syncthreads();
+    for (int a = tid; a < A; a += 256) {
+        int e = __hip_atomic_load(idx + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        e = min(max(e, 0), E - 1);
+        s_idx[a] = e;
+        atomicAdd(&s_cnt[e], 1);
+    }
+    for (int s = tid; s < n_shared; s += 256) s_cnt[E + s] = T;
+    __syncthreads();
+    // exclusive scan over 512 entries: two per thread, Hillis-Steele on the pair sums
+    const int c0 = s_cnt[2 * tid], c1 = s_cnt[2 * tid + 1];
+    s_scan[tid] = c0 + c1;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {
+        int v = (tid >= off) ? s_scan[tid - off] : 0;
+        __syncthreads();
+        s_scan[tid] += v;
+        __syncthreads();
+    }
+    const int excl = s_scan[tid] - (c0 + c1);
+    __syncthreads();
+    s_cnt[2 * tid] = excl;            // s_cnt now holds the offsets
+    s_cnt[2 * tid + 1] = excl + c0;
+    if (2 * tid < E_tot) { counts[2 * tid] = c0; offsets[2 * tid] = excl; }
+    if (2 * tid + 1 < E_tot) { counts[2 * tid + 1] = c1; offsets[2 * tid + 1] = excl + c0; }
+    if (tid == 0) offsets[E_tot] = A + n_shared * T;
+    __syncthreads();
+    for (int a = tid; a < A; a += 256) {
+        const int e = s_idx[a];
+        int rank = 0;
+        for (int b = 0; b < a; ++b) rank += (s_idx[b] == e);
+        perm[s_cnt[e] + rank] = a;
+    }
+    for (int a = A + tid; a < A + n_shared * T; a += 256) perm[a] = a;
+}
+
+// ---------------------------------------------------------------------------------------------
+// K1: gate logits + softmax + top-k (+ grouping by the last workgroup).  Grid = T, block = 256.
+// ---------------------------------------------------------------------------------------------
+template <typename WT>
+__device__ __forceinline__ void load8_weights(const WT* p, float (&o)[8]);
+template <>
+__device__ __forceinline__ void load8_weights<float>(const float* p, float (&o)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+template <>
+__device__ __forceinline__ void load8_weights<uint16_t>(const uint16_t* p, float (&o)[8]) {
+    const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[2 * i] = __builtin_bit_cast(float, v[i] << 16);
+        o[2 * i + 1] = __builtin_bit_cast(float, v[i] & 0xFFFF0000u);
+    }
+}
+
+template <typename WT>
+__global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict__ x, const WT* __restrict__ wg,
+                                                        int T, int E, int d, int k, int renorm,
+                                                        int32_t* __restrict__ idx_out, float* __restrict__ w_out,
+                                                        float* __restrict__ logits_out, int do_group, int n_shared,
+                                                        int32_t* counts, int32_t* offsets, int32_t* perm,
+                                                        int32_t* ticket) {
+    __shared__ float s_logit[SPMOE_MAX_EXPERTS];
+    __shared__ int s_idx[GROUP_MAX_A];
+    __shared__ int s_cnt[512];
+    __shared__ int s_scan[256];
+    __shared__ int s_last;
+
+    const int t = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* xt = x + (size_t)t * d;
+
+    // ---- gate logits: wave `wave` scores experts wave, wave+4, ...; lanes split d in chunks of 8
+    for (int e = wave; e < E; e += 4) {
+        const WT* we = wg + (size_t)e * d;
+        float acc = 0.f;
+        for (int j = lane * 8; j < d; j += 64 * 8) {
+            float wv[8];
+            load8_weights<WT>(we + j, wv);
+            const float4 xa = *reinterpret_cast<const float4*>(xt + j);
+            const float4 xb = *reinterpret_cast<const float4*>(xt + j + 4);
+            acc = fmaf(xa.x, wv[0], acc); acc = fmaf(xa.y, wv[1], acc);
+            acc = fmaf(xa.z, wv[2], acc); acc = fmaf(xa.w, wv[3], acc);
+            acc = fmaf(xb.x, wv[4], acc); acc = fmaf(xb.y, wv[5], acc);
+            acc = fmaf(xb.z, wv[6], acc); acc = fmaf(xb.w, wv[7], acc);
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) s_logit[e] = acc;
+    }
+    __syncthreads();
+
+    // ---- wave 0: softmax and k rounds of wave-wide argmax (lane l owns experts l and l + 64)
+    if (wave == 0) {
+        float v[2];
+        bool taken[2];
+        float lmax = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int e = lane + 64 * q;
+            float l = (e < E) ? s_logit[e] : -INFINITY;
+            if (e < E && logits_out) logits_out[(size_t)t * E + e] = l;
+            if (!(l == l)) l = -INFINITY;            // NaN never wins
+            v[q] = l;
+            taken[q] = !(e < E);
+            lmax = fmaxf(lmax, l);
+        }
+        const float m = wave_max(lmax);
+        float psum = 0.f;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) psum += (lane + 64 * q < E) ? expf(v[q] - m) : 0.f;
+        const float denom = wave_sum(psum);
+
+        int sel_i[SPMOE_MAX_TOPK];
+        float sel_p[SPMOE_MAX_TOPK];
+        float sel_sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < SPMOE_MAX_TOPK; ++r) {
+            sel_i[r] = 0; sel_p[r] = 0.f;
+            if (r < k) {
+                // best untaken candidate of this lane; the lower index wins a tie
+                float bv = -INFINITY;
+                int bi = INT_MAX;
+#pragma unroll
+                for (int q = 1; q >= 0; --q)
+                    if (!taken[q] && (v[q] >= bv)) { bv = v[q]; bi = lane + 64 * q; }
+                const float best = wave_max(bi == INT_MAX ? -INFINITY : bv);
+                int win;
+                if (E <= 64) {
+                    // one expert per lane: the lowest set bit of the ballot is the lowest index
+                    const unsigned long long b = __builtin_amdgcn_ballot_w64(bi != INT_MAX && bv == best);
+                    win = b ? (__builtin_ctzll(b)) : INT_MAX;
+                } else {
+                    win = wave_min_i((bi != INT_MAX && bv == best) ? bi : INT_MAX);
+                }
+                if (win == INT_MAX) win = 0;          // cannot happen for k <= E; keeps the index in range
+                if ((win & 63) == lane) {
+                    if (win >> 6) taken[1] = true; else taken[0] = true;
+                }
+                const float p = expf(best - m) / denom;
+                sel_i[r] = win;
+                sel_p[r] = p;
+                sel_sum += p;
+            }
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int r = 0; r < SPMOE_MAX_TOPK; ++r)
+                if (r < k) {
+                    idx_out[(size_t)t * k + r] = sel_i[r];
+                    w_out[(size_t)t * k + r] = renorm ? sel_p[r] / sel_sum : sel_p[r];
+                }
+        }
+    }
+    if (!do_group) return;
+
+    // ---- the last workgroup to arrive groups all assignments by expert
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        const int old = atomicAdd(ticket, 1);
+        s_last = (old == T - 1);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    group_assignments(idx_out, T, k, E, n_shared, counts, offsets, perm, s_idx, s_cnt, s_scan);
+    if (tid == 0) *ticket = 0;
+}
+
+// Stand-alone grouping of a routing result (one workgroup).
+__global__ __launch_bounds__(256) void permute_kernel(const int32_t* idx, int T, int k, int E, int32_t* counts,
+                                                      int32_t* offsets, int32_t* perm) {
+    __shared__ int s_idx[GROUP_MAX_A];
+    __shared__ int s_cnt[512];
+    __shared__ int s_scan[256];
+    group_assignments(idx, T, k, E, 0, counts, offsets, perm, s_idx, s_cnt, s_scan);
+}
+
+// ---------------------------------------------------------------------------------------------
+// K2 / K3: grouped skinny GEMM on MFMA.
+//
+// One workgroup = (one expert of the launch's list, one tile of <= 16 of its tokens, one N-tile of
+// 16 weight rows, one K-split).  Its W waves split the K range; wave w streams KSW k-steps (1 KiB
+// per matrix per k-step) with a register ring of PF steps, multiplies each 16x32 weight tile with
+// the 32x16 token tile it keeps in registers for its K range, and the W partial 16x16 results are
+// summed through LDS in wave order (deterministic).
+//
+// MODE_GU   : A = interleaved W_gate / W_up tiles, B = x rows gathered through perm (fp32 -> bf16 on
+//             load); epilogue h[a][n] = silu(g) * u stored as bf16.
+// MODE_DOWN : A = W_down tiles, B = h rows (bf16); epilogue ypart[split][a][n] = partial y (fp32).
+//
+// MFMA 16x16x32 operand layout used here: A lane l = row (l & 15), K = 8*(l >> 4) .. +7; B lane l =
+// column (l & 15), same K; D lane l = column (l & 15), rows 4*(l >> 4) .. +3.
+// ---------------------------------------------------------------------------------------------
+enum { MODE_GU = 0, MODE_DOWN = 1 };
+
+struct GemmParams {
+    const int32_t* offsets;
+    const int32_t* perm;
+    const float* x;       // MODE_GU input  [T][d]
+    uint16_t* h;          // [A_tot][f] bf16 bits: MODE_GU output, MODE_DOWN input
+    float* ypart;         // MODE_DOWN output [splits][A_tot][d]
+    int32_t T, k, d, f;
+    int32_t A_tot;        // T*k + n_shared*T
+    int32_t ks_total;     // k-steps of the contraction: d/32 (GU), f/32 (DOWN)
+    int32_t ks_split;     // k-steps per K-split (gridDim.z splits)
+    int32_t mt_tiles;     // token tiles per expert covered by gridDim.y (1 or 2)
+    int32_t waves;        // waves per workgroup
+};
+
+template <int MODE, int KSW, bool EXACT, int PF>
+__global__ __launch_bounds__((KSW > 16 ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list, const GemmParams p) {
+    constexpr int NMAT = (MODE == MODE_GU) ? 2 : 1;
+    extern __shared__ float s_red[];   // [waves][NMAT][64 lanes][4]
+
+    const int li = blockIdx.y / p.mt_tiles;
+    const int mt = blockIdx.y - li * p.mt_tiles;
+    const int e = list.id[li];
+    const int beg = p.offsets[e] + 16 * mt;
+    const int cnt = min(16, p.offsets[e + 1] - beg);
+    if (cnt <= 0) return;                              // uniform over the workgroup
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, kg = lane >> 4;
+    const int nt = blockIdx.x;
+    const int K = (MODE == MODE_GU) ? p.d : p.f;       // contraction length
+    const int N = (MODE == MODE_GU) ? p.f : p.d;       // output features
+
+    // this wave's k-step range inside the split
+    const int ks_lo = blockIdx.z * p.ks_split + wave * KSW;
+    const int ks_hi = min(min(ks_lo + KSW, (int)(blockIdx.z + 1) * p.ks_split), p.ks_total);
+    const int nks = EXACT ? KSW : max(ks_hi - ks_lo, 0);
+
+    // weight stream of this wave: tile (nt, ks) of matrix m sits at ((nt*ks_total + ks)*NMAT + m) KiB
+    const char* blob = static_cast<const char*>(list.blob[li]);
+    if (MODE == MODE_DOWN) blob += (size_t)2 * p.d * p.f * sizeof(uint16_t);
+    const bf16x8* wp = reinterpret_cast<const bf16x8*>(blob) + ((size_t)nt * p.ks_total + ks_lo) * (NMAT * 64) + lane;
+
+    bf16x8 ring[PF][NMAT];
+#pragma unroll
+    for (int j = 0; j < PF; ++j)
+        if (j < KSW && (EXACT || j < nks)) {
+#pragma unroll
+            for (int m = 0; m < NMAT; ++m) ring[j][m] = __builtin_nontemporal_load(wp + (size_t)j * (NMAT * 64) + m * 64);
+        }
+
+    // token tile (B operand) for this wave's K range, kept in registers
+    const int a_n = (n < cnt) ? p.perm[beg + n] : -1;
+    bf16x8 xr[KSW];
+    if (MODE == MODE_GU) {
+        const int routed = p.T * p.k;
+        const int tok = (a_n < 0) ? 0 : (a_n < routed ? a_n / p.k : (a_n - routed) % p.T);
+        const float* xrow = p.x + (size_t)tok * K + ks_lo * 32 + kg * 8;
+#pragma unroll
+        for (int j = 0; j < KSW; ++j) {
+            u32x4 packed = {0u, 0u, 0u, 0u};
+            if (a_n >= 0 && (EXACT || j < nks)) {
+                const float4 lo = *reinterpret_cast<const float4*>(xrow + j * 32);
+                const float4 hi = *reinterpret_cast<const float4*>(xrow + j * 32 + 4);
+                packed[0] = pack_bf16x2(lo.x, lo.y); packed[1] = pack_bf16x2(lo.z, lo.w);
+                packed[2] = pack_bf16x2(hi.x, hi.y); packed[3] = pack_bf16x2(hi.z, hi.w);
+            }
+            xr[j] = __builtin_bit_cast(bf16x8, packed);
+        }
+    } else {
+        const uint16_t* hrow = p.h + (size_t)max(a_n, 0) * K + ks_lo * 32 + kg * 8;
+#pragma unroll
+        for (int j = 0; j < KSW; ++j) {
+            u32x4 packed = {0u, 0u, 0u, 0u};
+            if (a_n >= 0 && (EXACT || j < nks)) packed = *reinterpret_cast<const u32x4*>(hrow + j * 32);
+            xr[j] = __builtin_bit_cast(bf16x8, packed);
+        }
+    }
+
+    f32x4 acc[NMAT];
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+    for (int j = 0; j < KSW; ++j) {
+        if (EXACT || j < nks) {
+            bf16x8 a[NMAT];
+#pragma unroll
+            for (int m = 0; m < NMAT; ++m) a[m] = ring[j % PF][m];
+            if (j + PF < KSW && (EXACT || j + PF < nks)) {
+#pragma unroll
+                for (int m = 0; m < NMAT; ++m)
+                    ring[j % PF][m] = __builtin_nontemporal_load(wp + (size_t)(j + PF) * (NMAT * 64) + m * 64);
+            }
+#pragma unroll
+            for (int m = 0; m < NMAT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], xr[j], acc[m], 0, 0, 0);
+        }
+    }
+
+    // cross-wave reduction through LDS, summed in wave order
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m)
+        *reinterpret_cast<f32x4*>(s_red + ((wave * NMAT + m) * 64 + lane) * 4) = acc[m];
+    __syncthreads();
+    for (int o = tid; o < 256; o += blockDim.x) {
+        // o -> (token on, feature fi) with consecutive threads on consecutive features
+        const int fi = o & 15, on = o >> 4;
+        if (on >= cnt) continue;
+        const int src = (((fi >> 2) * 16 + on) * 4) + (fi & 3);
+        float s0 = 0.f, s1 = 0.f;
+        for (int w = 0; w < p.waves; ++w) {
+            s0 += s_red[(w * NMAT) * 256 + src];
+            if (NMAT == 2) s1 += s_red[(w * NMAT + 1) * 256 + src];
+        }
+        const int a_o = p.perm[beg + on];
+        const int feat = nt * 16 + fi;
+        if (MODE == MODE_GU) {
+            const float hval = (s0 / (1.f + expf(-s0))) * s1;
+            p.h[(size_t)a_o * N + feat] = (uint16_t)f32_to_bf16_bits(hval);
+        } else {
+            p.ypart[((size_t)blockIdx.z * p.A_tot + a_o) * N + feat] = s0;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// fp32-weight variant on the vector ALU (small configurations).  Blob = W_gate[f][d], W_up[f][d],
+// W_down[d][f] row-major.  One wave per output row; tokens of the expert in chunks of 8.
+// h is fp32 [A_tot][f] here.
+// ---------------------------------------------------------------------------------------------
+template <int MODE>
+__global__ __launch_bounds__(256) void expert_gemm_f32_kernel(const SpmoeExpertList list, const GemmParams p,
+                                                              float* __restrict__ h32) {
+    const int li = blockIdx.y;
+    const int e = list.id[li];
+    const int beg = p.offsets[e], end = p.offsets[e + 1];
+    if (end <= beg) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int K = (MODE == MODE_GU) ? p.d : p.f;
+    const int N = (MODE == MODE_GU) ? p.f : p.d;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= N) return;
+    const float* blob = static_cast<const float*>(list.blob[li]);
+    const float* w0 = (MODE == MODE_GU) ? blob + (size_t)row * K : blob + (size_t)2 * p.d * p.f + (size_t)row * K;
+    const float* w1 = blob + (size_t)p.d * p.f + (size_t)row * K;   // W_up row (MODE_GU only)
+    const int routed = p.T * p.k;
+
+    for (int c = beg; c < end; c += 8) {
+        float a0[8], a1[8];
+        const float* xin[8];
+        int asg[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            a0[i] = 0.f; a1[i] = 0.f;
+            asg[i] = (c + i < end) ? p.perm[c + i] : -1;
+            const int a = max(asg[i], 0);
+            if (MODE == MODE_GU) {
+                const int tok = a < routed ? a / p.k : (a - routed) % p.T;
+                xin[i] = p.x + (size_t)tok * K;
+            } else {
+                xin[i] = h32 + (size_t)a * K;
+            }
+        }
+        for (int j = lane * 4; j < K; j += 256) {
+            const float4 wa = *reinterpret_cast<const float4*>(w0 + j);
+            float4 wb = {0.f, 0.f, 0.f, 0.f};
+            if (MODE == MODE_GU) wb = *reinterpret_cast<const float4*>(w1 + j);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (asg[i] < 0) continue;
+                const float4 xv = *reinterpret_cast<const float4*>(xin[i] + j);
+                a0[i] = fmaf(xv.x, wa.x, a0[i]); a0[i] = fmaf(xv.y, wa.y, a0[i]);
+                a0[i] = fmaf(xv.z, wa.z, a0[i]); a0[i] = fmaf(xv.w, wa.w, a0[i]);
+                if (MODE == MODE_GU) {
+                    a1[i] = fmaf(xv.x, wb.x, a1[i]); a1[i] = fmaf(xv.y, wb.y, a1[i]);
+                    a1[i] = fmaf(xv.z, wb.z, a1[i]); a1[i] = fmaf(xv.w, wb.w, a1[i]);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (asg[i] < 0) continue;                    // uniform over the wave
+            const float g = wave_sum(a0[i]);
+            if (MODE == MODE_GU) {
+                const float u = wave_sum(a1[i]);
+                if (lane == 0) h32[(size_t)asg[i] * N + row] = (g / (1.f + expf(-g))) * u;
+            } else {
+                if (lane == 0) p.ypart[(size_t)asg[i] * N + row] = g;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K4: weighted combination (Eq. 1).  out[t][j] = sum_r w[t][r] * y[t*k + r][j] + sum_s y[shared s, t][j]
+// where y[a] = sum over K-splits of ypart[split][a], every sum in ascending index order.
+// Grid = (ceil(d / 1024), T), block = 256, four columns per thread.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ ypart, const float* __restrict__ w,
+                                                      int T, int k, int n_shared, int d, int splits,
+                                                      float* __restrict__ out) {
+    const int t = blockIdx.y;
+    const int j = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (j >= d) return;
+    const int A_tot = T * k + n_shared * T;
+    float4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < k + n_shared; ++r) {
+        const int a = (r < k) ? t * k + r : T * k + (r - k) * T + t;
+        float4 y = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < splits; ++s) {
+            const float4 v = *reinterpret_cast<const float4*>(ypart + ((size_t)s * A_tot + a) * d + j);
+            y.x += v.x; y.y += v.y; y.z += v.z; y.w += v.w;
+        }
+        const float g = (r < k) ? w[t * k + r] : 1.f;
+        acc.x += g * y.x; acc.y += g * y.y; acc.z += g * y.z; acc.w += g * y.w;
+    }
+    *reinterpret_cast<float4*>(out + (size_t)t * d + j) = acc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+hipError_t spmoe_launch_gate_topk(hipStream_t stream, int dtype, const float* x, const void* wg, int T, int E, int d,
+                                  int k, int renorm, int32_t* idx, float* w, float* logits, int n_shared,
+                                  int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* ticket) {
+    const int do_group = counts != nullptr;
+    if (dtype == SPMOE_BF16)
+        hipLaunchKernelGGL(gate_topk_kernel<uint16_t>, dim3(T), dim3(256), 0, stream, x, static_cast<const uint16_t*>(wg),
+                           T, E, d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket);
+    else
+        hipLaunchKernelGGL(gate_topk_kernel<float>, dim3(T), dim3(256), 0, stream, x, static_cast<const float*>(wg), T, E,
+                           d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket);
+    return hipGetLastError();
+}
+
+hipError_t spmoe_launch_permute(hipStream_t stream, const int32_t* idx, int T, int k, int E, int32_t* counts,
+                                int32_t* offsets, int32_t* perm) {
+    hipLaunchKernelGGL(permute_kernel, dim3(1), dim3(256), 0, stream, idx, T, k, E, counts, offsets, perm);
+    return hipGetLastError();
+}
+
+// Factorisation of the contraction's k-steps into (K-splits) x (waves) x (k-steps per wave).
+struct GemmPlan {
+    int splits, waves, ksw;
+    bool exact;
+};
+
+static const int kExactKsw[] = {32, 28, 24, 16, 14, 12, 11, 8, 4};
+static const int kWavePreference[] = {8, 16, 4, 12, 10, 6, 14, 2, 1};
+
+static bool is_exact_ksw(int ksw) {
+    for (int v : kExactKsw)
+        if (v == ksw) return true;
+    return false;
+}
+
+// Workgroups of more than 8 waves leave 128 VGPRs per lane, enough for 16 k-steps of token tile.
+static bool plan_ok(int waves, int ksw) { return ksw <= 16 || waves <= 8; }
+
+static GemmPlan plan_gemm(int ks_total, int max_splits) {
+    for (int splits = 1; splits <= max_splits; splits *= 2) {
+        if (ks_total % splits) break;
+        const int per = ks_total / splits;
+        for (int waves : kWavePreference) {
+            if (per % waves) continue;
+            const int ksw = per / waves;
+            if (is_exact_ksw(ksw) && plan_ok(waves, ksw)) return GemmPlan{splits, waves, ksw, true};
+        }
+    }
+    // generic instance: up to 8 waves of at most 32 k-steps each, more K-splits for longer contractions
+    int splits = 1;
+    while ((ks_total + splits - 1) / splits > 8 * 32) ++splits;
+    const int per = (ks_total + splits - 1) / splits;
+    return GemmPlan{splits, (per + 31) / 32, 32, false};
+}
+
+int spmoe_down_splits(int dtype, int d, int f) {
+    (void)d;
+    if (dtype != SPMOE_BF16) return 1;
+    return plan_gemm(f / 32, 4).splits;
+}
+
+template <int MODE>
+static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, dim3 grid, const SpmoeExpertList& list,
+                                   const GemmParams& p) {
+    const dim3 block(plan.waves * 64);
+    const size_t lds = (size_t)plan.waves * (MODE == MODE_GU ? 2 : 1) * 256 * sizeof(float);
+    constexpr int PF = (MODE == MODE_GU) ? 4 : 8;
+#define SPMOE_GEMM_CASE(KSW_)                                                                                   \
+    case KSW_:                                                                                                  \
+        hipLaunchKernelGGL((expert_gemm_kernel<MODE, KSW_, true, PF>), grid, block, lds, stream, list, p);      \
+        break;
+    if (plan.exact) {
+        switch (plan.ksw) {
+            SPMOE_GEMM_CASE(32) SPMOE_GEMM_CASE(28) SPMOE_GEMM_CASE(24) SPMOE_GEMM_CASE(16) SPMOE_GEMM_CASE(14)
+            SPMOE_GEMM_CASE(12) SPMOE_GEMM_CASE(11) SPMOE_GEMM_CASE(8) SPMOE_GEMM_CASE(4)
+            default: return hipErrorInvalidValue;
+        }
+    } else {
+        hipLaunchKernelGGL((expert_gemm_kernel<MODE, 32, false, PF>), grid, block, lds, stream, list, p);
+    }
+#undef SPMOE_GEMM_CASE
+    return hipGetLastError();
+}
+
+static GemmParams make_params(const SpmoeShape& s, const SpmoeRouting& r) {
+    GemmParams p;
+    p.offsets = r.offsets;
+    p.perm = r.perm;
+    p.x = nullptr;
+    p.h = nullptr;
+    p.ypart = nullptr;
+    p.T = s.T; p.k = s.k; p.d = s.d; p.f = s.f;
+    p.A_tot = s.T * s.k + s.n_shared * s.T;
+    p.ks_total = 0; p.ks_split = 0;
+    p.mt_tiles = (s.T > 16) ? 2 : 1;
+    p.waves = 4;
+    return p;
+}
+
+hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape& s, const SpmoeExpertList& list,
+                                const SpmoeRouting& r, const float* x, void* h) {
+    if (list.n <= 0) return hipSuccess;
+    GemmParams p = make_params(s, r);
+    p.x = x;
+    p.h = static_cast<uint16_t*>(h);
+    if (dtype == SPMOE_BF16) {
+        const GemmPlan plan = plan_gemm(s.d / 32, 1);
+        p.ks_total = s.d / 32;
+        p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
+        p.waves = plan.waves;
+        return launch_gemm_bf16<MODE_GU>(stream, plan, dim3(s.f / 16, list.n * p.mt_tiles, 1), list, p);
+    }
+    hipLaunchKernelGGL(expert_gemm_f32_kernel<MODE_GU>, dim3((s.f + 3) / 4, list.n), dim3(256), 0, stream, list, p,
+                       static_cast<float*>(h));
+    return hipGetLastError();
+}
+
+hipError_t spmoe_launch_down(hipStream_t stream, int dtype, const SpmoeShape& s, const SpmoeExpertList& list,
+                             const SpmoeRouting& r, const void* h, float* ypart, int splits) {
+    if (list.n <= 0) return hipSuccess;
+    GemmParams p = make_params(s, r);
+    p.h = static_cast<uint16_t*>(const_cast<void*>(h));
+    p.ypart = ypart;
+    if (dtype == SPMOE_BF16) {
+        const GemmPlan plan = plan_gemm(s.f / 32, 4);
+        if (plan.splits != splits) return hipErrorInvalidValue;
+        p.ks_total = s.f / 32;
+        p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
+        p.waves = plan.waves;
+        return launch_gemm_bf16<MODE_DOWN>(stream, plan, dim3(s.d / 16, list.n * p.mt_tiles, plan.splits), list, p);
+    }
+    hipLaunchKernelGGL(expert_gemm_f32_kernel<MODE_DOWN>, dim3((s.d + 3) / 4, list.n), dim3(256), 0, stream, list, p,
+                       static_cast<float*>(const_cast<void*>(h)));
+    return hipGetLastError();
+}
+
+hipError_t spmoe_launch_combine(hipStream_t stream, const SpmoeShape& s, const SpmoeRouting& r, const float* ypart,
+                                int splits, float* out) {
+    hipLaunchKernelGGL(combine_kernel, dim3((s.d + 1023) / 1024, s.T), dim3(256), 0, stream, ypart, r.w, s.T, s.k,
+                       s.n_shared, s.d, splits, out);
+    return hipGetLastError();
+}

@@ -1,0 +1,777 @@
+// Host runtime of libspmoe: contexts, the per-layer LRU expert cache (Q_cache), the copy stream and
+// the slot events that order copies against kernels, the prediction / prefetch entry points (Alg. 1,
+// Alg. 2) and the verify-layer orchestration (cached experts first, missing ones on demand).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "spmoe_internal.h"
+
+namespace {
+
+struct Slot {
+    void* dev = nullptr;
+    int expert = -1;              // routed expert id held, -1 = empty
+    hipEvent_t ready = nullptr;   // recorded on the copy stream after the slot's last copy
+    hipEvent_t freed = nullptr;   // recorded on the compute stream after the last kernel that reads the slot
+    bool ready_pending = false;   // a copy was issued and not yet known to have finished
+    bool freed_valid = false;     // `freed` has been recorded since the slot was last written
+    bool unused_prefetch = false; // filled by spmoe_prefetch and not yet used by a verify pass
+    uint64_t copy_seq = 0;        // issue order of the slot's last copy
+};
+
+struct Layer {
+    const void* gate = nullptr;
+    std::vector<const void*> host_blob;   // [E] pinned packed blobs (borrowed)
+    std::vector<int> slot_of;             // [E] slot index or -1
+    std::vector<int> lru;                 // resident experts, head (front) = least recently used
+    std::vector<Slot> slots;              // [cache_slots_per_layer]
+    std::vector<void*> shared_dev;        // [n_shared] HBM copies of the shared experts
+};
+
+struct TimedSpan {
+    hipEvent_t begin, end;
+    int kind, layer, expert;
+};
+
+}  // namespace
+
+struct spmoe_ctx {
+    spmoe_config cfg;
+    hipStream_t compute = nullptr;
+    hipStream_t copy = nullptr;
+    size_t blob_bytes = 0;
+    std::vector<Layer> layers;
+    spmoe_stats stats;
+    uint64_t copy_seq = 0;
+    std::string err;
+
+    // device scratch
+    SpmoeRouting route{};
+    SpmoeRouting pred{};          // routing scratch of spmoe_predict_experts
+    void* h = nullptr;            // [A_tot_max][f] bf16 (fp32 for fp32 weights)
+    float* ypart = nullptr;       // [splits][A_tot_max][d]
+    int down_splits = 1;
+    int a_tot_max = 0;
+
+    // pinned host staging for the few integers the host needs
+    int32_t* host_counts = nullptr;   // [E]
+    int32_t* host_pred_idx = nullptr; // [Tmax * pred_k]
+    float* host_pred_p = nullptr;     // [Tmax * pred_k]
+    hipEvent_t host_ready = nullptr;
+
+    // profiling
+    bool profiling = false;
+    hipEvent_t prof_origin = nullptr;
+    std::vector<TimedSpan> spans;
+    hipEvent_t kev[8] = {};          // kernel-boundary events of the last profiled verify call
+    std::vector<TimedSpan> kspans;   // kernel spans of the last profiled verify call (kind = kernel index)
+};
+
+namespace {
+
+spmoe_status fail(spmoe_ctx* c, spmoe_status st, const char* fmt, ...) {
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return st;
+}
+
+#define HIP_TRY(c, call)                                                                       \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess) return fail((c), SPMOE_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+bool config_ok(const spmoe_config* c, const char** why) {
+    if (!c) { *why = "config is NULL"; return false; }
+    if (c->weight_dtype != SPMOE_F32 && c->weight_dtype != SPMOE_BF16) { *why = "weight_dtype"; return false; }
+    if (c->n_layers < 1) { *why = "n_layers < 1"; return false; }
+    if (c->d_model < 32 || c->d_model % 32 || c->d_ff < 32 || c->d_ff % 32) { *why = "d_model and d_ff must be positive multiples of 32"; return false; }
+    if (c->weight_dtype == SPMOE_BF16 && c->d_model > 8192) { *why = "d_model > 8192"; return false; }
+    if (c->n_experts < 1 || c->n_experts > SPMOE_MAX_EXPERTS) { *why = "n_experts out of range"; return false; }
+    if (c->top_k < 1 || c->top_k > SPMOE_MAX_TOPK || c->top_k > c->n_experts) { *why = "top_k out of range"; return false; }
+    if (c->n_shared < 0 || c->n_shared > SPMOE_MAX_SHARED) { *why = "n_shared out of range"; return false; }
+    if (c->max_tokens < 1 || c->max_tokens > SPMOE_MAX_TOKENS) { *why = "max_tokens out of range"; return false; }
+    if (c->cache_slots_per_layer < 1 || c->cache_slots_per_layer > c->n_experts) { *why = "cache_slots_per_layer out of range"; return false; }
+    if (c->pred_k < 0 || c->pred_k > SPMOE_MAX_TOPK || c->pred_k > c->n_experts) { *why = "pred_k out of range"; return false; }
+    return true;
+}
+
+size_t elem_bytes(int dtype) { return dtype == SPMOE_BF16 ? 2 : 4; }
+
+void lru_touch(Layer& L, int expert) {
+    auto it = std::find(L.lru.begin(), L.lru.end(), expert);
+    if (it != L.lru.end()) L.lru.erase(it);
+    L.lru.push_back(expert);
+}
+
+// Picks the slot a new expert goes to: an empty one, else the LRU head's (which is evicted).
+int take_slot(spmoe_ctx* c, Layer& L) {
+    for (size_t s = 0; s < L.slots.size(); ++s)
+        if (L.slots[s].expert < 0) return (int)s;
+    const int victim = L.lru.front();
+    L.lru.erase(L.lru.begin());
+    const int s = L.slot_of[victim];
+    L.slot_of[victim] = -1;
+    c->stats.evictions += 1;
+    if (L.slots[s].unused_prefetch) {
+        c->stats.prefetch_wasted += 1;
+        L.slots[s].unused_prefetch = false;
+    }
+    L.slots[s].expert = -1;
+    return s;
+}
+
+spmoe_status span_begin(spmoe_ctx* c, hipStream_t st, int kind, int layer, int expert, size_t* id) {
+    *id = (size_t)-1;
+    if (!c->profiling) return SPMOE_OK;
+    TimedSpan sp{nullptr, nullptr, kind, layer, expert};
+    HIP_TRY(c, hipEventCreate(&sp.begin));
+    HIP_TRY(c, hipEventCreate(&sp.end));
+    HIP_TRY(c, hipEventRecord(sp.begin, st));
+    c->spans.push_back(sp);
+    *id = c->spans.size() - 1;
+    return SPMOE_OK;
+}
+spmoe_status span_end(spmoe_ctx* c, hipStream_t st, size_t id) {
+    if (id == (size_t)-1) return SPMOE_OK;
+    HIP_TRY(c, hipEventRecord(c->spans[id].end, st));
+    return SPMOE_OK;
+}
+
+// Issues the copy of `expert` into slot s on the copy stream (waits for the slot's last reader first).
+spmoe_status issue_copy(spmoe_ctx* c, int layer, int expert, int s, bool prefetch) {
+    Layer& L = c->layers[layer];
+    Slot& sl = L.slots[s];
+    if (sl.freed_valid) {
+        HIP_TRY(c, hipStreamWaitEvent(c->copy, sl.freed, 0));
+        sl.freed_valid = false;
+    }
+    size_t span;
+    spmoe_status st = span_begin(c, c->copy, prefetch ? 1 : 2, layer, expert, &span);
+    if (st != SPMOE_OK) return st;
+    HIP_TRY(c, hipMemcpyAsync(sl.dev, L.host_blob[expert], c->blob_bytes, hipMemcpyHostToDevice, c->copy));
+    st = span_end(c, c->copy, span);
+    if (st != SPMOE_OK) return st;
+    HIP_TRY(c, hipEventRecord(sl.ready, c->copy));
+    sl.ready_pending = true;
+    sl.copy_seq = ++c->copy_seq;
+    sl.expert = expert;
+    sl.unused_prefetch = prefetch;
+    L.slot_of[expert] = s;
+    L.lru.push_back(expert);
+    if (prefetch) {
+        c->stats.prefetch_issued += 1;
+        c->stats.h2d_bytes_prefetch += (int64_t)c->blob_bytes;
+    } else {
+        c->stats.ondemand_loads += 1;
+        c->stats.h2d_bytes_ondemand += (int64_t)c->blob_bytes;
+    }
+    return SPMOE_OK;
+}
+
+bool copy_done(Slot& sl) {
+    if (!sl.ready_pending) return true;
+    if (hipEventQuery(sl.ready) == hipSuccess) {
+        sl.ready_pending = false;
+        return true;
+    }
+    (void)hipGetLastError();   // hipErrorNotReady is not an error here
+    return false;
+}
+
+SpmoeShape shape_of(const spmoe_ctx* c, int T) {
+    return SpmoeShape{T, c->cfg.top_k, c->cfg.n_experts, c->cfg.n_shared, c->cfg.d_model, c->cfg.d_ff};
+}
+
+void kernel_mark(spmoe_ctx* c, int i) {
+    if (c->profiling && c->kev[i]) (void)hipEventRecord(c->kev[i], c->compute);
+}
+
+// One launch of the two expert GEMMs for the experts in `list`, timed per kernel when profiling.
+spmoe_status launch_experts(spmoe_ctx* c, const SpmoeShape& sh, const SpmoeExpertList& list, const float* x) {
+    if (list.n <= 0) return SPMOE_OK;
+    TimedSpan k2{nullptr, nullptr, 1, 0, list.n}, k3{nullptr, nullptr, 2, 0, list.n};
+    if (c->profiling) {
+        HIP_TRY(c, hipEventCreate(&k2.begin));
+        HIP_TRY(c, hipEventCreate(&k2.end));
+        HIP_TRY(c, hipEventCreate(&k3.end));
+        k3.begin = k2.end;
+        HIP_TRY(c, hipEventRecord(k2.begin, c->compute));
+    }
+    HIP_TRY(c, spmoe_launch_gate_up(c->compute, c->cfg.weight_dtype, sh, list, c->route, x, c->h));
+    if (c->profiling) HIP_TRY(c, hipEventRecord(k2.end, c->compute));
+    HIP_TRY(c, spmoe_launch_down(c->compute, c->cfg.weight_dtype, sh, list, c->route, c->h, c->ypart, c->down_splits));
+    if (c->profiling) {
+        HIP_TRY(c, hipEventRecord(k3.end, c->compute));
+        c->kspans.push_back(k2);
+        c->kspans.push_back(k3);
+    }
+    return SPMOE_OK;
+}
+
+void free_kspans(spmoe_ctx* c) {
+    for (auto& s : c->kspans) {
+        if (s.kind == 1) { (void)hipEventDestroy(s.begin); (void)hipEventDestroy(s.end); }
+        else (void)hipEventDestroy(s.end);   // kind 2 shares its begin with the preceding kind-1 span's end
+    }
+    c->kspans.clear();
+}
+
+void free_spans(spmoe_ctx* c) {
+    for (auto& s : c->spans) { (void)hipEventDestroy(s.begin); (void)hipEventDestroy(s.end); }
+    c->spans.clear();
+}
+
+spmoe_status check_layer(spmoe_ctx* c, int layer) {
+    if (!c) return SPMOE_EINVAL;
+    if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, SPMOE_ERANGE, "layer %d out of range [0, %d)", layer, c->cfg.n_layers);
+    return SPMOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t spmoe_expert_blob_bytes(const spmoe_config* cfg) {
+    const char* why;
+    if (!config_ok(cfg, &why)) return 0;
+    return (size_t)3 * cfg->d_model * cfg->d_ff * elem_bytes(cfg->weight_dtype);
+}
+
+spmoe_status spmoe_pack_expert(const spmoe_config* cfg, const void* host_w_gate, const void* host_w_up,
+                               const void* host_w_down, void* host_blob_out) {
+    const char* why;
+    if (!config_ok(cfg, &why) || !host_w_gate || !host_w_up || !host_w_down || !host_blob_out) return SPMOE_EINVAL;
+    const size_t d = cfg->d_model, f = cfg->d_ff;
+    if (cfg->weight_dtype == SPMOE_F32) {
+        char* o = static_cast<char*>(host_blob_out);
+        memcpy(o, host_w_gate, d * f * 4);
+        memcpy(o + d * f * 4, host_w_up, d * f * 4);
+        memcpy(o + 2 * d * f * 4, host_w_down, d * f * 4);
+        return SPMOE_OK;
+    }
+    // bf16: 8-element (16-byte) chunks are moved into 16x32 tiles in MFMA A-operand lane order.
+    struct Chunk { uint64_t lo, hi; };
+    const Chunk* g = static_cast<const Chunk*>(host_w_gate);
+    const Chunk* u = static_cast<const Chunk*>(host_w_up);
+    const Chunk* dn = static_cast<const Chunk*>(host_w_down);
+    Chunk* out = static_cast<Chunk*>(host_blob_out);
+    {   // gate / up: rows n in [0,f), contraction over d; tiles interleaved gate, up
+        const size_t ks_total = d / 32, chunks_per_row = d / 8;
+        #pragma omp parallel for schedule(static)
+        for (size_t n = 0; n < f; ++n) {
+            const size_t nt = n / 16, r = n % 16;
+            for (size_t cidx = 0; cidx < chunks_per_row; ++cidx) {
+                const size_t ks = cidx / 4, kg = cidx % 4, lane = kg * 16 + r;
+                const size_t tile = (nt * ks_total + ks) * 2;
+                out[(tile + 0) * 64 + lane] = g[n * chunks_per_row + cidx];
+                out[(tile + 1) * 64 + lane] = u[n * chunks_per_row + cidx];
+            }
+        }
+    }
+    {   // down: rows i in [0,d), contraction over f
+        Chunk* od = out + (2 * d * f) / 8;
+        const size_t ks_total = f / 32, chunks_per_row = f / 8;
+        #pragma omp parallel for schedule(static)
+        for (size_t i = 0; i < d; ++i) {
+            const size_t nt = i / 16, r = i % 16;
+            for (size_t cidx = 0; cidx < chunks_per_row; ++cidx) {
+                const size_t ks = cidx / 4, kg = cidx % 4, lane = kg * 16 + r;
+                od[(nt * ks_total + ks) * 64 + lane] = dn[i * chunks_per_row + cidx];
+            }
+        }
+    }
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_ctx** out) {
+    const char* why = "";
+    if (!out) return SPMOE_EINVAL;
+    if (!config_ok(cfg, &why)) {
+        if (cfg && (cfg->n_experts > SPMOE_MAX_EXPERTS || cfg->max_tokens > SPMOE_MAX_TOKENS || cfg->top_k > SPMOE_MAX_TOPK))
+            return SPMOE_ERANGE;
+        return SPMOE_EINVAL;
+    }
+    spmoe_ctx* c = new (std::nothrow) spmoe_ctx();
+    if (!c) return SPMOE_ENOMEM;
+    c->cfg = *cfg;
+    c->compute = static_cast<hipStream_t>(compute_stream);
+    c->blob_bytes = spmoe_expert_blob_bytes(cfg);
+    memset(&c->stats, 0, sizeof c->stats);
+    const int E = cfg->n_experts, S = cfg->cache_slots_per_layer, Tm = cfg->max_tokens;
+    const int E_tot = E + cfg->n_shared;
+    c->a_tot_max = Tm * cfg->top_k + cfg->n_shared * Tm;
+    c->down_splits = spmoe_down_splits(cfg->weight_dtype, cfg->d_model, cfg->d_ff);
+
+#define CREATE_TRY(call)                                                             \
+    do {                                                                             \
+        hipError_t e_ = (call);                                                      \
+        if (e_ != hipSuccess) {                                                      \
+            const bool oom = (e_ == hipErrorOutOfMemory);                            \
+            (void)hipGetLastError();                                                 \
+            spmoe_destroy(c);                                                        \
+            return oom ? SPMOE_ENOMEM : SPMOE_EHIP;                                  \
+        }                                                                            \
+    } while (0)
+
+    CREATE_TRY(hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking));
+    CREATE_TRY(hipEventCreateWithFlags(&c->host_ready, hipEventDisableTiming));
+    const int pk = std::max(cfg->pred_k, 1);
+    auto alloc_routing = [&](SpmoeRouting& r, int k) -> hipError_t {
+        hipError_t e;
+        if ((e = hipMalloc(&r.idx, sizeof(int32_t) * Tm * k)) != hipSuccess) return e;
+        if ((e = hipMalloc(&r.w, sizeof(float) * Tm * k)) != hipSuccess) return e;
+        if ((e = hipMalloc(&r.logits, sizeof(float) * Tm * E)) != hipSuccess) return e;
+        if ((e = hipMalloc(&r.counts, sizeof(int32_t) * E_tot)) != hipSuccess) return e;
+        if ((e = hipMalloc(&r.offsets, sizeof(int32_t) * (E_tot + 1))) != hipSuccess) return e;
+        if ((e = hipMalloc(&r.perm, sizeof(int32_t) * (Tm * k + cfg->n_shared * Tm))) != hipSuccess) return e;
+        if ((e = hipMalloc(&r.ticket, sizeof(int32_t))) != hipSuccess) return e;
+        return hipMemset(r.ticket, 0, sizeof(int32_t));
+    };
+    CREATE_TRY(alloc_routing(c->route, cfg->top_k));
+    CREATE_TRY(alloc_routing(c->pred, pk));
+    CREATE_TRY(hipMalloc(&c->h, (size_t)c->a_tot_max * cfg->d_ff * (cfg->weight_dtype == SPMOE_BF16 ? 2 : 4)));
+    CREATE_TRY(hipMalloc(&c->ypart, sizeof(float) * (size_t)c->down_splits * c->a_tot_max * cfg->d_model));
+    CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->host_counts), sizeof(int32_t) * E_tot, hipHostMallocDefault));
+    CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->host_pred_idx), sizeof(int32_t) * Tm * pk, hipHostMallocDefault));
+    CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->host_pred_p), sizeof(float) * Tm * pk, hipHostMallocDefault));
+
+    c->layers.resize(cfg->n_layers);
+    for (auto& L : c->layers) {
+        L.host_blob.assign(E, nullptr);
+        L.slot_of.assign(E, -1);
+        L.slots.resize(S);
+        L.shared_dev.assign(cfg->n_shared, nullptr);
+    }
+    for (auto& L : c->layers) {
+        for (auto& sl : L.slots) {
+            CREATE_TRY(hipMalloc(&sl.dev, c->blob_bytes));
+            CREATE_TRY(hipEventCreateWithFlags(&sl.ready, hipEventDisableTiming));
+            CREATE_TRY(hipEventCreateWithFlags(&sl.freed, hipEventDisableTiming));
+        }
+        for (auto& p : L.shared_dev) CREATE_TRY(hipMalloc(&p, c->blob_bytes));
+    }
+#undef CREATE_TRY
+    *out = c;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_destroy(spmoe_ctx* c) {
+    if (!c) return SPMOE_OK;
+    (void)hipStreamSynchronize(c->compute);
+    if (c->copy) (void)hipStreamSynchronize(c->copy);
+    free_spans(c);
+    free_kspans(c);
+    for (auto& e : c->kev) if (e) (void)hipEventDestroy(e);
+    if (c->prof_origin) (void)hipEventDestroy(c->prof_origin);
+    for (auto& L : c->layers) {
+        for (auto& sl : L.slots) {
+            if (sl.dev) (void)hipFree(sl.dev);
+            if (sl.ready) (void)hipEventDestroy(sl.ready);
+            if (sl.freed) (void)hipEventDestroy(sl.freed);
+        }
+        for (auto& p : L.shared_dev) if (p) (void)hipFree(p);
+    }
+    auto free_routing = [](SpmoeRouting& r) {
+        (void)hipFree(r.idx); (void)hipFree(r.w); (void)hipFree(r.logits); (void)hipFree(r.counts);
+        (void)hipFree(r.offsets); (void)hipFree(r.perm); (void)hipFree(r.ticket);
+    };
+    free_routing(c->route);
+    free_routing(c->pred);
+    (void)hipFree(c->h);
+    (void)hipFree(c->ypart);
+    if (c->host_counts) (void)hipHostFree(c->host_counts);
+    if (c->host_pred_idx) (void)hipHostFree(c->host_pred_idx);
+    if (c->host_pred_p) (void)hipHostFree(c->host_pred_p);
+    if (c->host_ready) (void)hipEventDestroy(c->host_ready);
+    if (c->copy) (void)hipStreamDestroy(c->copy);
+    delete c;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_sync(spmoe_ctx* c) {
+    if (!c) return SPMOE_EINVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->copy));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    return SPMOE_OK;
+}
+
+const char* spmoe_last_error(const spmoe_ctx* c) { return c ? c->err.c_str() : ""; }
+
+spmoe_status spmoe_set_gate(spmoe_ctx* c, int layer, const void* dev_wg) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (!dev_wg) return fail(c, SPMOE_EINVAL, "gate pointer is NULL");
+    c->layers[layer].gate = dev_wg;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_set_cutoff(spmoe_ctx* c, int cutoff_layer) {
+    if (!c) return SPMOE_EINVAL;
+    c->cfg.cutoff_layer = cutoff_layer;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_expert_cache_register(spmoe_ctx* c, int layer, int expert, const void* pinned_blob) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (expert < 0 || expert >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", expert);
+    if (!pinned_blob) return fail(c, SPMOE_EINVAL, "blob pointer is NULL");
+    c->layers[layer].host_blob[expert] = pinned_blob;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_expert_cache_register_shared(spmoe_ctx* c, int layer, int idx, const void* pinned_blob) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (idx < 0 || idx >= c->cfg.n_shared) return fail(c, SPMOE_ERANGE, "shared expert %d out of range", idx);
+    if (!pinned_blob) return fail(c, SPMOE_EINVAL, "blob pointer is NULL");
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    HIP_TRY(c, hipMemcpy(c->layers[layer].shared_dev[idx], pinned_blob, c->blob_bytes, hipMemcpyHostToDevice));
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_expert_cache_warm(spmoe_ctx* c, int layer, const int32_t* host_experts, int n) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (n < 0 || (n > 0 && !host_experts)) return fail(c, SPMOE_EINVAL, "bad expert list");
+    Layer& L = c->layers[layer];
+    for (int i = 0; i < n; ++i) {
+        const int e = host_experts[i];
+        if (e < 0 || e >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", e);
+        if (!L.host_blob[e]) return fail(c, SPMOE_ESTATE, "expert %d of layer %d is not registered", e, layer);
+    }
+    for (int i = 0; i < n; ++i) {
+        const int e = host_experts[i];
+        if (L.slot_of[e] >= 0) { lru_touch(L, e); continue; }
+        const int s = take_slot(c, L);
+        st = issue_copy(c, layer, e, s, false);
+        if (st != SPMOE_OK) return st;
+        L.slots[s].unused_prefetch = false;
+        // warm-up is bookkeeping-neutral: it is neither a prefetch nor a verify-time miss
+        c->stats.ondemand_loads -= 1;
+        c->stats.h2d_bytes_ondemand -= (int64_t)c->blob_bytes;
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->copy));
+    for (auto& sl : L.slots) sl.ready_pending = false;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_expert_cache_lookup(spmoe_ctx* c, int layer, int expert, int32_t* host_slot_out) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (expert < 0 || expert >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", expert);
+    if (!host_slot_out) return fail(c, SPMOE_EINVAL, "output pointer is NULL");
+    *host_slot_out = c->layers[layer].slot_of[expert];
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_expert_cache_contents(spmoe_ctx* c, int layer, int32_t* host_lru_order_out, int32_t* host_n_out) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (!host_lru_order_out || !host_n_out) return fail(c, SPMOE_EINVAL, "output pointer is NULL");
+    const Layer& L = c->layers[layer];
+    for (size_t i = 0; i < L.lru.size(); ++i) host_lru_order_out[i] = L.lru[i];
+    *host_n_out = (int32_t)L.lru.size();
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_expert_cache_reset(spmoe_ctx* c) {
+    if (!c) return SPMOE_EINVAL;
+    spmoe_status st = spmoe_sync(c);
+    if (st != SPMOE_OK) return st;
+    for (auto& L : c->layers) {
+        L.lru.clear();
+        std::fill(L.slot_of.begin(), L.slot_of.end(), -1);
+        for (auto& sl : L.slots) {
+            sl.expert = -1;
+            sl.ready_pending = false;
+            sl.freed_valid = false;
+            sl.unused_prefetch = false;
+        }
+    }
+    memset(&c->stats, 0, sizeof c->stats);
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_expert_cache_stats(spmoe_ctx* c, spmoe_stats* host_out) {
+    if (!c) return SPMOE_EINVAL;
+    if (!host_out) return fail(c, SPMOE_EINVAL, "output pointer is NULL");
+    *host_out = c->stats;
+    return SPMOE_OK;
+}
+
+// ---- hot path -------------------------------------------------------------------------------------
+
+spmoe_status spmoe_gate_topk(spmoe_ctx* c, int layer, const float* dev_x, int T, int k, int32_t* dev_idx, float* dev_w,
+                             float* dev_logits) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (!dev_x || !dev_idx || !dev_w) return fail(c, SPMOE_EINVAL, "NULL device pointer");
+    if (T < 0 || T > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "T=%d exceeds max_tokens=%d", T, c->cfg.max_tokens);
+    if (k < 1 || k > SPMOE_MAX_TOPK || k > c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "k=%d out of range", k);
+    if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
+    if (T == 0) return SPMOE_OK;
+    HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_x, c->layers[layer].gate, T, c->cfg.n_experts,
+                                      c->cfg.d_model, k, c->cfg.renorm_topk, dev_idx, dev_w, dev_logits, 0, nullptr,
+                                      nullptr, nullptr, nullptr));
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_token_permutation(spmoe_ctx* c, const int32_t* dev_idx, int T, int k, int32_t* dev_counts,
+                                     int32_t* dev_offsets, int32_t* dev_perm) {
+    if (!c) return SPMOE_EINVAL;
+    if (!dev_idx || !dev_counts || !dev_offsets || !dev_perm) return fail(c, SPMOE_EINVAL, "NULL device pointer");
+    if (T < 0 || T > SPMOE_MAX_TOKENS) return fail(c, SPMOE_ERANGE, "T=%d out of range", T);
+    if (k < 1 || k > SPMOE_MAX_TOPK) return fail(c, SPMOE_ERANGE, "k=%d out of range", k);
+    HIP_TRY(c, spmoe_launch_permute(c->compute, dev_idx, T, k, c->cfg.n_experts, dev_counts, dev_offsets, dev_perm));
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_predict_experts(spmoe_ctx* c, int layer, const float* dev_draft_x, int n, int32_t* host_ids_out,
+                                   int32_t* host_n_out) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (!dev_draft_x || !host_ids_out || !host_n_out) return fail(c, SPMOE_EINVAL, "NULL pointer");
+    if (n < 0 || n > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "n=%d exceeds max_tokens=%d", n, c->cfg.max_tokens);
+    if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer || n == 0 || c->cfg.pred_k < 1) {   // Alg. 1: only l <= L
+        *host_n_out = 0;
+        return SPMOE_OK;
+    }
+    Layer& L = c->layers[layer];
+    if (!L.gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
+    const int pk = c->cfg.pred_k, E = c->cfg.n_experts;
+    size_t span;
+    st = span_begin(c, c->compute, 3, layer, n, &span);
+    if (st != SPMOE_OK) return st;
+    // plain softmax probabilities (no renormalisation) rank experts predicted by several draft tokens
+    HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_draft_x, L.gate, n, E, c->cfg.d_model, pk, 0,
+                                      c->pred.idx, c->pred.w, nullptr, 0, nullptr, nullptr, nullptr, nullptr));
+    HIP_TRY(c, hipMemcpyAsync(c->host_pred_idx, c->pred.idx, sizeof(int32_t) * n * pk, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(c->host_pred_p, c->pred.w, sizeof(float) * n * pk, hipMemcpyDeviceToHost, c->compute));
+    st = span_end(c, c->compute, span);
+    if (st != SPMOE_OK) return st;
+    HIP_TRY(c, hipEventRecord(c->host_ready, c->compute));
+    HIP_TRY(c, hipEventSynchronize(c->host_ready));
+
+    int votes[SPMOE_MAX_EXPERTS] = {0};
+    double psum[SPMOE_MAX_EXPERTS] = {0.0};
+    for (int i = 0; i < n * pk; ++i) {
+        const int e = c->host_pred_idx[i];
+        if (e < 0 || e >= E) return fail(c, SPMOE_EHIP, "prediction kernel returned expert %d", e);
+        votes[e] += 1;
+        psum[e] += c->host_pred_p[i];
+    }
+    std::vector<int> order;
+    for (int e = 0; e < E; ++e)
+        if (votes[e] > 0) order.push_back(e);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        if (votes[a] != votes[b]) return votes[a] > votes[b];
+        if (psum[a] != psum[b]) return psum[a] > psum[b];
+        return a < b;
+    });
+    int m = 0;
+    for (int e : order) {
+        if (L.slot_of[e] < 0) host_ids_out[m++] = e;   // Alg. 1: predicted experts that are already cached are dropped ...
+        else lru_touch(L, e);                          // ... and moved to the tail, so this task cannot evict them
+    }
+    *host_n_out = m;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_prefetch(spmoe_ctx* c, int layer, const int32_t* host_experts, int n) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (n < 0 || (n > 0 && !host_experts)) return fail(c, SPMOE_EINVAL, "bad expert list");
+    Layer& L = c->layers[layer];
+    for (int i = 0; i < n; ++i) {
+        const int e = host_experts[i];
+        if (e < 0 || e >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", e);
+        if (!L.host_blob[e]) return fail(c, SPMOE_ESTATE, "expert %d of layer %d is not registered", e, layer);
+    }
+    if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer) return SPMOE_OK;   // Alg. 1: only l <= L
+    std::vector<int> uniq;
+    for (int i = 0; i < n; ++i)
+        if (std::find(uniq.begin(), uniq.end(), host_experts[i]) == uniq.end()) uniq.push_back(host_experts[i]);
+    if ((int)uniq.size() > c->cfg.cache_slots_per_layer) uniq.resize(c->cfg.cache_slots_per_layer);
+    for (int e : uniq)
+        if (L.slot_of[e] >= 0) lru_touch(L, e);        // predicted and cached: moved to the tail, not loaded
+    for (int e : uniq) {                               // Alg. 2: as many victims as loads, copies back to back
+        if (L.slot_of[e] >= 0) continue;
+        const int s = take_slot(c, L);
+        st = issue_copy(c, layer, e, s, true);
+        if (st != SPMOE_OK) return st;
+    }
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x, int T, float* dev_out) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (!dev_x || !dev_out) return fail(c, SPMOE_EINVAL, "NULL device pointer");
+    if (T < 0 || T > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "T=%d exceeds max_tokens=%d", T, c->cfg.max_tokens);
+    Layer& L = c->layers[layer];
+    if (!L.gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
+    if (T == 0) return SPMOE_OK;
+    const int E = c->cfg.n_experts, dt = c->cfg.weight_dtype;
+    const SpmoeShape sh = shape_of(c, T);
+
+    if (c->profiling) {
+        free_kspans(c);
+        for (auto& e : c->kev) if (!e) HIP_TRY(c, hipEventCreate(&e));
+    }
+    size_t span;
+    st = span_begin(c, c->compute, 0, layer, 0, &span);
+    if (st != SPMOE_OK) return st;
+
+    kernel_mark(c, 0);
+    HIP_TRY(c, spmoe_launch_gate_topk(c->compute, dt, dev_x, L.gate, T, E, c->cfg.d_model, c->cfg.top_k,
+                                      c->cfg.renorm_topk, c->route.idx, c->route.w, c->route.logits, c->cfg.n_shared,
+                                      c->route.counts, c->route.offsets, c->route.perm, c->route.ticket));
+    kernel_mark(c, 1);
+
+    SpmoeExpertList list;
+    list.n = 0;
+    auto add = [&](int id, const void* blob) { list.id[list.n] = (uint16_t)id; list.blob[list.n] = blob; list.n += 1; };
+
+    if ((int)L.lru.size() == E) {
+        // every routed expert is resident: no routing information is needed on the host
+        for (int s = 0; s < c->cfg.n_shared; ++s) add(E + s, L.shared_dev[s]);
+        for (int e = 0; e < E; ++e) {
+            Slot& sl = L.slots[L.slot_of[e]];
+            if (!copy_done(sl)) HIP_TRY(c, hipStreamWaitEvent(c->compute, sl.ready, 0));
+            add(e, sl.dev);
+        }
+        st = launch_experts(c, sh, list, dev_x);
+        if (st != SPMOE_OK) return st;
+    } else {
+        // offloaded experts: the per-expert token counts decide which experts this batch needs
+        HIP_TRY(c, hipMemcpyAsync(c->host_counts, c->route.counts, sizeof(int32_t) * E, hipMemcpyDeviceToHost, c->compute));
+        HIP_TRY(c, hipEventRecord(c->host_ready, c->compute));
+        HIP_TRY(c, hipEventSynchronize(c->host_ready));
+        std::vector<int> hits, misses;
+        for (int e = 0; e < E; ++e) {
+            if (c->host_counts[e] <= 0) continue;
+            if (L.slot_of[e] >= 0) hits.push_back(e);
+            else {
+                if (!L.host_blob[e]) return fail(c, SPMOE_ESTATE, "expert %d of layer %d is needed but not registered", e, layer);
+                misses.push_back(e);
+            }
+        }
+        c->stats.hits += (int64_t)hits.size();
+        c->stats.misses += (int64_t)misses.size();
+        // cached experts first ("Computation Implementation"): those whose data has landed in one launch,
+        // then the ones still in flight in the order their copies were issued
+        std::vector<int> landed, inflight;
+        for (int e : hits) {
+            Slot& sl = L.slots[L.slot_of[e]];
+            lru_touch(L, e);
+            if (sl.unused_prefetch) { sl.unused_prefetch = false; c->stats.prefetch_used += 1; }
+            if (copy_done(sl)) landed.push_back(e);
+            else { inflight.push_back(e); c->stats.late_hits += 1; }
+        }
+        std::sort(inflight.begin(), inflight.end(), [&](int a, int b) {
+            return L.slots[L.slot_of[a]].copy_seq < L.slots[L.slot_of[b]].copy_seq;
+        });
+        for (int s = 0; s < c->cfg.n_shared; ++s) add(E + s, L.shared_dev[s]);
+        for (int e : landed) add(e, L.slots[L.slot_of[e]].dev);
+        st = launch_experts(c, sh, list, dev_x);
+        if (st != SPMOE_OK) return st;
+        for (int e : landed) {
+            Slot& sl = L.slots[L.slot_of[e]];
+            HIP_TRY(c, hipEventRecord(sl.freed, c->compute));
+            sl.freed_valid = true;
+        }
+        auto run_one = [&](int e) -> spmoe_status {
+            Slot& sl = L.slots[L.slot_of[e]];
+            HIP_TRY(c, hipStreamWaitEvent(c->compute, sl.ready, 0));
+            list.n = 0;
+            add(e, sl.dev);
+            spmoe_status s2 = launch_experts(c, sh, list, dev_x);
+            if (s2 != SPMOE_OK) return s2;
+            HIP_TRY(c, hipEventRecord(sl.freed, c->compute));
+            sl.freed_valid = true;
+            return SPMOE_OK;
+        };
+        for (int e : inflight) {
+            st = run_one(e);
+            if (st != SPMOE_OK) return st;
+        }
+        // missing experts: loaded on demand into the LRU head's slot, computed as each copy lands
+        for (int e : misses) {
+            const int s = take_slot(c, L);
+            st = issue_copy(c, layer, e, s, false);
+            if (st != SPMOE_OK) return st;
+            st = run_one(e);
+            if (st != SPMOE_OK) return st;
+        }
+    }
+    kernel_mark(c, 2);
+    HIP_TRY(c, spmoe_launch_combine(c->compute, sh, c->route, c->ypart, c->down_splits, dev_out));
+    kernel_mark(c, 3);
+    return span_end(c, c->compute, span);
+}
+
+// ---- measurement ------------------------------------------------------------------------------------
+
+spmoe_status spmoe_profile_begin(spmoe_ctx* c) {
+    if (!c) return SPMOE_EINVAL;
+    free_spans(c);
+    if (!c->prof_origin) HIP_TRY(c, hipEventCreate(&c->prof_origin));
+    HIP_TRY(c, hipStreamSynchronize(c->copy));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    HIP_TRY(c, hipEventRecord(c->prof_origin, c->compute));
+    HIP_TRY(c, hipStreamWaitEvent(c->copy, c->prof_origin, 0));
+    c->profiling = true;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_profile_collect(spmoe_ctx* c, spmoe_profile_record* host_out, int cap, int* host_n_out) {
+    if (!c) return SPMOE_EINVAL;
+    if (!host_n_out || (cap > 0 && !host_out)) return fail(c, SPMOE_EINVAL, "NULL output pointer");
+    c->profiling = false;
+    spmoe_status st = spmoe_sync(c);
+    if (st != SPMOE_OK) return st;
+    const int n = (int)c->spans.size();
+    for (int i = 0; i < n && i < cap; ++i) {
+        const TimedSpan& s = c->spans[i];
+        float b = 0.f, e = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&b, c->prof_origin, s.begin));
+        HIP_TRY(c, hipEventElapsedTime(&e, c->prof_origin, s.end));
+        host_out[i] = spmoe_profile_record{s.kind, s.layer, s.expert, 0, b, e};
+    }
+    *host_n_out = n;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_last_layer_kernel_ms(spmoe_ctx* c, float host_ms_out[4]) {
+    if (!c) return SPMOE_EINVAL;
+    if (!host_ms_out) return fail(c, SPMOE_EINVAL, "NULL output pointer");
+    if (!c->kev[0]) return fail(c, SPMOE_ESTATE, "no verify-layer call has run with profiling on");
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    float ms[4] = {0.f, 0.f, 0.f, 0.f};
+    HIP_TRY(c, hipEventElapsedTime(&ms[0], c->kev[0], c->kev[1]));
+    HIP_TRY(c, hipEventElapsedTime(&ms[3], c->kev[2], c->kev[3]));
+    for (const auto& s : c->kspans) {
+        float t = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&t, s.begin, s.end));
+        ms[s.kind] += t;
+    }
+    for (int i = 0; i < 4; ++i) host_ms_out[i] = ms[i];
+    return SPMOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+"""GPU tests of the expert cache, prediction and prefetch: results never depend on the cache state
+(policy invariance), and the bookkeeping matches the reference cache/queue model call by call."""
+import numpy as np
+import pytest
+
+import spmoe_inputs as si
+from oracle.cache_model import CacheModel
+from parity_util import REL_L2_BF16, gpu_layer, oracle_layer, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(slots, cutoff, layers=3, E=8, k=2, d=256, f=192, T=8, pred_k=2, shared=0, seed=12):
+    from paper_2510_10302_amd import workload as W
+    wl = W.Workload(d=d, f=f, E=E, k=k, shared=shared, dtype="bf16", layers=layers, seed=seed, gate_std=0.05, std=0.05)
+    L = W.Loaded(wl, W.make_config(wl, max_tokens=T, slots=slots, cutoff_layer=cutoff, pred_k=pred_k))
+    return wl, L
+
+
+def test_policy_invariance_outputs_do_not_depend_on_cache_state():
+    T = 8
+    wl, ref = _setup(slots=None, cutoff=-1)
+    xs = [si.hidden(12, T, 256, iteration=i, layer=l) for i in range(3) for l in range(3)]
+    want = [gpu_layer(ref, j % 3, x)["out"] for j, x in enumerate(xs)]
+    ref.close()
+    for slots in (1, 2, 3, 5):
+        wl2, L = _setup(slots=slots, cutoff=1)
+        rng = np.random.default_rng(slots)
+        for j, x in enumerate(xs):
+            layer = j % 3
+            L.ctx.prefetch(layer, rng.integers(0, 8, size=3).tolist())     # arbitrary (mostly wrong) prefetches
+            got = gpu_layer(L, layer, x)["out"]
+            assert np.array_equal(got, want[j]), (slots, j)                 # bit-identical: fixed summation order
+        st = L.ctx.expert_cache_stats()
+        assert st["misses"] == st["ondemand_loads"] and st["hits"] + st["misses"] > 0
+        L.close()
+
+
+def test_bookkeeping_matches_cache_model(oracle32):
+    T, E, k, slots, cutoff, n_layers = 8, 8, 2, 3, 1, 3
+    wl, L = _setup(slots=slots, cutoff=cutoff, layers=n_layers)
+    model = CacheModel(n_layers, E, slots, cutoff_layer=cutoff)
+    import torch
+    for it in range(4):
+        for layer in range(n_layers):
+            x = si.hidden(12, T, 256, iteration=it, layer=layer)
+            draft = x + si.draft_noise(12, T, 256, 0.3, iteration=it, layer=layer)
+            # Alg. 1 on the library ...
+            ids = L.ctx.predict_experts(layer, torch.from_numpy(draft).cuda())
+            # ... and on the reference: top-pred_k per draft token, ranked by votes / probability / index
+            if layer <= cutoff:
+                pidx, plog, pp = oracle32.predict_experts(draft, wl.gate[layer], 2)
+                votes = np.bincount(pidx.reshape(-1), minlength=E)
+                psum = np.zeros(E)
+                for t in range(T):
+                    for e in pidx[t]:
+                        psum[e] += pp[t, e]
+                ranked = sorted([e for e in range(E) if votes[e]], key=lambda e: (-votes[e], -psum[e], e))
+                assert ids == model.filter_cached(layer, ranked)
+            else:
+                assert ids == []
+            L.ctx.prefetch(layer, ids)
+            model.prefetch(layer, ids)
+            assert L.ctx.expert_cache_contents(layer) == model.contents(layer)
+        for layer in range(n_layers):
+            x = si.hidden(12, T, 256, iteration=it, layer=layer)
+            g = gpu_layer(L, layer, x)
+            ref = oracle_layer(oracle32, wl, layer, x)
+            assert np.array_equal(g["idx"], ref["idx"])
+            assert rel_l2(g["out"], ref["out"]) < REL_L2_BF16
+            model.verify(layer, sorted(set(ref["idx"].reshape(-1).tolist())))
+            assert L.ctx.expert_cache_contents(layer) == model.contents(layer), (it, layer)
+            for e in range(E):
+                assert (L.ctx.expert_cache_lookup(layer, e) >= 0) == (e in model.contents(layer))
+    st = L.ctx.expert_cache_stats()
+    for key in ("hits", "misses", "evictions", "prefetch_issued", "prefetch_used", "prefetch_wasted", "ondemand_loads"):
+        assert st[key] == model.stats[key], (key, st, model.stats)
+    nbytes = 3 * 256 * 192 * 2
+    assert st["h2d_bytes_prefetch"] == st["prefetch_issued"] * nbytes
+    assert st["h2d_bytes_ondemand"] == st["ondemand_loads"] * nbytes
+    L.ctx.expert_cache_reset()
+    assert L.ctx.expert_cache_contents(0) == [] and L.ctx.expert_cache_stats()["hits"] == 0
+    L.close()
+
+
+def test_shared_experts_with_offload(oracle32):
+    # DeepSeek-like arity, offloaded routed experts, shared experts always resident
+    wl, L = _setup(slots=16, cutoff=1, layers=2, E=64, k=6, d=256, f=160, T=16, pred_k=6, shared=2, seed=13)
+    import torch
+    for layer in range(2):
+        x = si.hidden(13, 16, 256, layer=layer)
+        ids = L.ctx.predict_experts(layer, torch.from_numpy(x).cuda())   # sigma = 0: prediction is the truth
+        L.ctx.prefetch(layer, ids)
+        g = gpu_layer(L, layer, x)
+        ref = oracle_layer(oracle32, wl, layer, x)
+        assert np.array_equal(g["idx"], ref["idx"])
+        assert rel_l2(g["out"], ref["out"]) < REL_L2_BF16
+    st = L.ctx.expert_cache_stats()
+    assert st["prefetch_used"] == st["prefetch_issued"] == 32 and st["hits"] >= 32
+    L.close()
+
+
+def test_profile_records_cover_copies_and_layers():
+    wl, L = _setup(slots=2, cutoff=0, layers=2)
+    import torch
+    L.ctx.profile_begin()
+    L.ctx.prefetch(0, [1, 2])
+    x = torch.from_numpy(si.hidden(12, 8, 256)).cuda()
+    out = torch.empty((8, 256), device="cuda")
+    L.ctx.moe_verify_layer(0, x, out)
+    ms = L.ctx.last_layer_kernel_ms()
+    recs = L.ctx.profile_collect()
+    kinds = [r["kind"] for r in recs]
+    assert kinds.count(1) == 2 and kinds.count(0) == 1 and kinds.count(2) >= 1
+    assert all(r["t1"] >= r["t0"] >= 0 for r in recs)
+    assert len(ms) == 4 and all(m >= 0 for m in ms) and ms[1] > 0 and ms[2] > 0
+    L.close()

@@ -1,0 +1,166 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import spmoe_inputs as si
+from parity_util import (REL_L2_BF16, REL_L2_F32, check_layer, gpu_layer, oracle_layer, rel_l2, routing_report)
+
+pytestmark = pytest.mark.gpu
+
+
+def _loaded(wl, T, slots=None, **kw):
+    from paper_2510_10302_amd import workload as W
+    return W.Loaded(wl, W.make_config(wl, max_tokens=T, slots=slots, **kw))
+
+
+def _wl(**kw):
+    from paper_2510_10302_amd import workload as W
+    return W.Workload(**kw)
+
+
+def test_c1_small_fp32(oracle32, oracle64):
+    # BASELINE config 1: d_model 512, d_ff 1024, 8 experts top-2, 5 tokens, fp32 weights, seed 0, all resident
+    wl = _wl(d=512, f=1024, E=8, k=2, shared=0, dtype="f32", layers=1, seed=0)
+    L = _loaded(wl, 5)
+    x = si.hidden(0, 5, 512)
+    g = gpu_layer(L, 0, x)
+    rep = check_layer(g, oracle_layer(oracle32, wl, 0, x), 2, REL_L2_F32)
+    assert rel_l2(g["out"], oracle_layer(oracle64, wl, 0, x)["out"]) < REL_L2_F32
+    print("c1", rep)
+    L.close()
+
+
+@pytest.mark.parametrize("d,f,E,k,shared,T", [
+    (256, 416, 8, 2, 0, 11),      # ragged: 13 k-steps in the down projection, odd token count
+    (512, 1408, 64, 6, 2, 16),    # DeepSeek-like routing arity with shared experts
+    (128, 96, 4, 2, 0, 32),       # experts with more than 16 tokens: two token tiles
+    (2048, 192, 8, 2, 0, 8),      # exact-plan gate/up (64 k-steps), generic down
+    (1024, 8192, 2, 1, 0, 3),     # long contraction in the down projection: generic plan with K-splits
+    (64, 64, 1, 1, 0, 1),         # a single expert, a single token
+])
+def test_mid_size_bf16_full_compare(d, f, E, k, shared, T, oracle32):
+    wl = _wl(d=d, f=f, E=E, k=k, shared=shared, dtype="bf16", layers=1, seed=3, gate_std=0.05, std=0.05)
+    L = _loaded(wl, T)
+    x = si.hidden(3, T, d)
+    rep = check_layer(gpu_layer(L, 0, x), oracle_layer(oracle32, wl, 0, x), k, REL_L2_BF16)
+    print((d, f, E, k, shared, T), rep)
+    L.close()
+
+
+def test_c2_mixtral_layer_full_size(oracle32):
+    # BASELINE config 2 in the configuration bench.py times: d=4096, f=14336, 8 experts top-2, bf16, 8 tokens
+    wl = _wl(d=4096, f=14336, E=8, k=2, shared=0, dtype="bf16", layers=1, seed=0)
+    L = _loaded(wl, 8)
+    x = si.hidden(0, 8, 4096)
+    g = gpu_layer(L, 0, x)
+    ref = oracle_layer(oracle32, wl, 0, x)
+    rep = check_layer(g, ref, 2, REL_L2_BF16)
+    print("c2", rep)
+    # per-token error as well: no single token may hide behind the aggregate
+    for t in range(8):
+        assert rel_l2(g["out"][t], ref["out"][t]) < REL_L2_BF16
+    L.close()
+
+
+def test_all_tokens_to_one_expert_and_k_equals_E(oracle32):
+    # degenerate routing: a gate whose row 2 dominates sends every token to expert 2 first
+    wl = _wl(d=128, f=96, E=4, k=4, shared=0, dtype="bf16", layers=1, seed=5, gate_std=0.05, std=0.05)
+    L = _loaded(wl, 16)
+    x = si.hidden(5, 16, 128)
+    g = gpu_layer(L, 0, x)
+    rep = check_layer(g, oracle_layer(oracle32, wl, 0, x), 4, REL_L2_BF16)
+    assert sorted(g["idx"][0].tolist()) == [0, 1, 2, 3]
+    print(rep)
+    L.close()
+
+
+def test_exact_ties_pick_lower_index(oracle32):
+    # duplicate gate rows give bit-identical logits on both sides: the lower index must win
+    import torch
+    from paper_2510_10302_amd import workload as W
+    wl = _wl(d=128, f=96, E=8, k=2, shared=0, dtype="bf16", layers=1, seed=6, gate_std=0.05, std=0.05)
+    wl.gate[0][5] = wl.gate[0][1]
+    wl.gate[0][6] = wl.gate[0][1]
+    L = _loaded(wl, 8)
+    x = si.hidden(6, 8, 128)
+    g = gpu_layer(L, 0, x)
+    ref = oracle_layer(oracle32, wl, 0, x)
+    assert np.array_equal(g["idx"], ref["idx"])
+    for t in range(8):
+        row = g["idx"][t].tolist()
+        if 5 in row:
+            assert 1 in row and row.index(1) < row.index(5)
+        assert 6 not in row or (1 in row and 5 in row)
+    L.close()
+
+
+def test_zero_tokens_is_a_noop_and_errors_are_reported():
+    import torch
+    from paper_2510_10302_amd import SpmoeError
+    wl = _wl(d=64, f=64, E=4, k=2, shared=0, dtype="bf16", layers=2, seed=1)
+    L = _loaded(wl, 4)
+    out = torch.full((0, 64), 1.0, device="cuda")
+    L.ctx.moe_verify_layer(0, torch.zeros((0, 64), device="cuda"), out)
+    x5 = torch.zeros((5, 64), device="cuda")
+    with pytest.raises(SpmoeError) as e:
+        L.ctx.moe_verify_layer(0, x5, torch.zeros((5, 64), device="cuda"))      # T > max_tokens
+    assert e.value.status_name == "SPMOE_ERANGE"
+    with pytest.raises(SpmoeError) as e:
+        L.ctx.moe_verify_layer(2, x5[:4], torch.zeros((4, 64), device="cuda"))  # layer out of range
+    assert e.value.status_name == "SPMOE_ERANGE"
+    with pytest.raises(SpmoeError) as e:
+        L.ctx.prefetch(0, [7])
+    assert e.value.status_name == "SPMOE_ERANGE"
+    with pytest.raises(SpmoeError) as e:
+        L.ctx.gate_topk(0, x5[:4], 5, torch.zeros((4, 5), dtype=torch.int32, device="cuda"),
+                        torch.zeros((4, 5), device="cuda"))                         # k > E
+    assert e.value.status_name == "SPMOE_ERANGE"
+    L.close()
+
+
+def test_token_permutation_matches_oracle(oracle32):
+    import torch
+    wl = _wl(d=64, f=64, E=64, k=6, shared=0, dtype="bf16", layers=1, seed=2)
+    L = _loaded(wl, 32)
+    rng = np.random.default_rng(4)
+    for T in (1, 7, 16, 32):
+        idx = np.stack([rng.choice(64, size=6, replace=False) for _ in range(T)]).astype(np.int32)
+        d_idx = torch.from_numpy(idx).cuda()
+        counts = torch.zeros(64, dtype=torch.int32, device="cuda")
+        offsets = torch.zeros(65, dtype=torch.int32, device="cuda")
+        perm = torch.zeros(T * 6, dtype=torch.int32, device="cuda")
+        L.ctx.token_permutation(d_idx, counts, offsets, perm)
+        L.ctx.sync()
+        rc, ro, rp = oracle32.permute(idx, 64)
+        assert np.array_equal(counts.cpu().numpy(), rc)
+        assert np.array_equal(offsets.cpu().numpy(), ro)
+        assert np.array_equal(perm.cpu().numpy(), rp)
+    L.close()
+
+
+def test_gate_topk_many_tokens_bit_exact(oracle32):
+    # routing alone on many independent batches: indices bit-exact outside near-ties, which are listed
+    import torch
+    for (E, k, d) in [(8, 2, 4096), (64, 6, 2048), (16, 2, 4096), (128, 8, 256)]:
+        wl = _wl(d=d, f=64, E=E, k=k, shared=0, dtype="bf16", layers=1, seed=8)
+        L = _loaded(wl, 32)
+        exact = near_total = 0
+        for it in range(6):
+            x = si.hidden(8, 32, d, iteration=it)
+            dx = torch.from_numpy(x).cuda()
+            idx = torch.zeros((32, k), dtype=torch.int32, device="cuda")
+            w = torch.zeros((32, k), device="cuda")
+            lg = torch.zeros((32, E), device="cuda")
+            L.ctx.gate_topk(0, dx, k, idx, w, lg)
+            L.ctx.sync()
+            ref_logits = oracle32.gate_logits(x, wl.gate[0])
+            ref_idx, ref_w = oracle32.route(ref_logits, k)
+            ex, near, bad = routing_report(idx.cpu().numpy(), ref_idx, ref_logits, k)
+            assert not bad
+            exact += ex
+            near_total += len(near)
+            good = [t for t in range(32) if t not in near]
+            assert np.abs(w.cpu().numpy()[good] - ref_w[good]).max() < 2e-5
+        print("gate_topk", (E, k, d), "exact", exact, "near-ties", near_total)
+        assert exact >= 6 * 32 - 2
+        L.close()

@@ -327,20 +327,25 @@ __global__ __launch_bounds__((KSW > 16 ? 8 : 16) * 64) void expert_gemm_kernel(c
     // this wave's k-step range inside the split
     const int ks_lo = blockIdx.z * p.ks_split + wave * KSW;
     const int ks_hi = min(min(ks_lo + KSW, (int)(blockIdx.z + 1) * p.ks_split), p.ks_total);
-    const int nks = EXACT ? KSW : max(ks_hi - ks_lo, 0);
+    // number of k-steps this wave really has: KSW for an exact plan, fewer (wave-uniform) otherwise.
+    // Steps beyond nks run with all-zero operands, so the MFMA chain below has no branches.
+    const int nks = EXACT ? KSW : __builtin_amdgcn_readfirstlane(max(ks_hi - ks_lo, 0));
 
     // weight stream of this wave: tile (nt, ks) of matrix m sits at ((nt*ks_total + ks)*NMAT + m) KiB
     const char* blob = static_cast<const char*>(list.blob[li]);
     if (MODE == MODE_DOWN) blob += (size_t)2 * p.d * p.f * sizeof(uint16_t);
     const bf16x8* wp = reinterpret_cast<const bf16x8*>(blob) + ((size_t)nt * p.ks_total + ks_lo) * (NMAT * 64) + lane;
+    const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
 
     bf16x8 ring[PF][NMAT];
 #pragma unroll
-    for (int j = 0; j < PF; ++j)
-        if (j < KSW && (EXACT || j < nks)) {
+    for (int j = 0; j < PF; ++j) {
 #pragma unroll
-            for (int m = 0; m < NMAT; ++m) ring[j][m] = __builtin_nontemporal_load(wp + (size_t)j * (NMAT * 64) + m * 64);
+        for (int m = 0; m < NMAT; ++m) {
+            ring[j][m] = zero8;
+            if (j < KSW && (EXACT || j < nks)) ring[j][m] = __builtin_nontemporal_load(wp + (size_t)j * (NMAT * 64) + m * 64);
         }
+    }
 
     // token tile (B operand) for this wave's K range, kept in registers
     const int a_n = (n < cnt) ? p.perm[beg + n] : -1;
@@ -376,18 +381,19 @@ __global__ __launch_bounds__((KSW > 16 ? 8 : 16) * 64) void expert_gemm_kernel(c
 
 #pragma unroll
     for (int j = 0; j < KSW; ++j) {
-        if (EXACT || j < nks) {
-            bf16x8 a[NMAT];
+        bf16x8 a[NMAT];
 #pragma unroll
-            for (int m = 0; m < NMAT; ++m) a[m] = ring[j % PF][m];
-            if (j + PF < KSW && (EXACT || j + PF < nks)) {
+        for (int m = 0; m < NMAT; ++m) a[m] = ring[j % PF][m];
+        if (j + PF < KSW) {
 #pragma unroll
-                for (int m = 0; m < NMAT; ++m)
+            for (int m = 0; m < NMAT; ++m) {
+                ring[j % PF][m] = zero8;
+                if (EXACT || j + PF < nks)
                     ring[j % PF][m] = __builtin_nontemporal_load(wp + (size_t)(j + PF) * (NMAT * 64) + m * 64);
             }
-#pragma unroll
-            for (int m = 0; m < NMAT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], xr[j], acc[m], 0, 0, 0);
         }
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], xr[j], acc[m], 0, 0, 0);
     }
 
     // cross-wave reduction through LDS, summed in wave order

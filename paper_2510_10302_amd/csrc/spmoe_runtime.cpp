@@ -339,7 +339,9 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
         if ((e = hipMalloc(&r.offsets, sizeof(int32_t) * (E_tot + 1))) != hipSuccess) return e;
         if ((e = hipMalloc(&r.perm, sizeof(int32_t) * (Tm * k + cfg->n_shared * Tm))) != hipSuccess) return e;
         if ((e = hipMalloc(&r.ticket, sizeof(int32_t))) != hipSuccess) return e;
-        return hipMemset(r.ticket, 0, sizeof(int32_t));
+        // the arrival counter must be zero before the first routing kernel: clear it on the compute stream
+        if ((e = hipMemsetAsync(r.ticket, 0, sizeof(int32_t), c->compute)) != hipSuccess) return e;
+        return hipStreamSynchronize(c->compute);
     };
     CREATE_TRY(alloc_routing(c->route, cfg->top_k));
     CREATE_TRY(alloc_routing(c->pred, pk));
@@ -520,11 +522,11 @@ spmoe_status spmoe_gate_topk(spmoe_ctx* c, int layer, const float* dev_x, int T,
                              float* dev_logits) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
-    if (!dev_x || !dev_idx || !dev_w) return fail(c, SPMOE_EINVAL, "NULL device pointer");
     if (T < 0 || T > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "T=%d exceeds max_tokens=%d", T, c->cfg.max_tokens);
     if (k < 1 || k > SPMOE_MAX_TOPK || k > c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "k=%d out of range", k);
+    if (T == 0) return SPMOE_OK;   // an empty batch is a no-op (its pointers may be NULL)
+    if (!dev_x || !dev_idx || !dev_w) return fail(c, SPMOE_EINVAL, "NULL device pointer");
     if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
-    if (T == 0) return SPMOE_OK;
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_x, c->layers[layer].gate, T, c->cfg.n_experts,
                                       c->cfg.d_model, k, c->cfg.renorm_topk, dev_idx, dev_w, dev_logits, 0, nullptr,
                                       nullptr, nullptr, nullptr));
@@ -621,11 +623,11 @@ spmoe_status spmoe_prefetch(spmoe_ctx* c, int layer, const int32_t* host_experts
 spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x, int T, float* dev_out) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
-    if (!dev_x || !dev_out) return fail(c, SPMOE_EINVAL, "NULL device pointer");
     if (T < 0 || T > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "T=%d exceeds max_tokens=%d", T, c->cfg.max_tokens);
+    if (T == 0) return SPMOE_OK;   // an empty batch is a no-op (its pointers may be NULL)
+    if (!dev_x || !dev_out) return fail(c, SPMOE_EINVAL, "NULL device pointer");
     Layer& L = c->layers[layer];
     if (!L.gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
-    if (T == 0) return SPMOE_OK;
     const int E = c->cfg.n_experts, dt = c->cfg.weight_dtype;
     const SpmoeShape sh = shape_of(c, T);
 
@@ -775,3 +777,4 @@ spmoe_status spmoe_last_layer_kernel_ms(spmoe_ctx* c, float host_ms_out[4]) {
 }
 
 }  // extern "C"
+

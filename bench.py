@@ -24,6 +24,19 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def profiled_traffic(workload, key):
+    """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by a copy-kernel calibration) and recorded in profiles/verify_layer_<workload>.txt; None if absent."""
+    path = os.path.join(ROOT, "profiles", "verify_layer_%s.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith(key + ":"):
+                return int(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,6 +45,8 @@ def main():
     ap.add_argument("--workload", default="c2_mixtral_8x7b")
     ap.add_argument("--batches", type=int, default=20, help="distinct synthetic token batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
+                    help="only run N plain 1 GiB device copies (counter calibration for rocprofv3 --pmc) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (the path would shard by expert across GPUs, "
@@ -47,6 +62,15 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        # a copy kernel of known traffic: reads 1 GiB, writes 1 GiB per launch (fp32 elementwise copy)
+        src = torch.ones(2 ** 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.calibrate_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": args.calibrate_copy, "bytes_read": 2 ** 30, "bytes_written": 2 ** 30}))
+        return
     spec = dict(W.CONFIGS[args.workload])
     d, f, E, k, T = spec["d"], spec["f"], spec["E"], spec["k"], spec["T"]
     n_shared = spec["shared"]
@@ -128,7 +152,8 @@ def main():
         "kernels_ms": {"route": float(kms[0]), "gate_up": float(kms[1]), "down": float(kms[2]), "combine": float(kms[3])},
         "expert_gemm_gbs": {"gate_up": gu_gbs, "down": dn_gbs, "both": both_gbs},
         "roofline": {"bound": "hbm", "kernel": "expert_gemm_kernel<gate_up>", "achieved": gu_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "traffic": None},
+                     "unit": "GB/s", "frac": gu_gbs / HBM_PEAK_GBS, "algorithmic_bytes": bytes_gu,
+                     "traffic": profiled_traffic(args.workload, "gate_up_traffic_bytes_per_launch")},
     }
 
     if not args.no_cpu_baseline:

@@ -37,6 +37,147 @@ def profiled_traffic(workload, key):
     return None
 
 
+def union(intervals):
+    """Sorted, merged copy of a list of (t0, t1)."""
+    out = []
+    for a, b in sorted(intervals):
+        if out and a <= out[-1][1]:
+            out[-1][1] = max(out[-1][1], b)
+        else:
+            out.append([a, b])
+    return out
+
+
+def measure(intervals):
+    return sum(b - a for a, b in intervals)
+
+
+def intersect(u1, u2):
+    """Total overlap of two merged interval lists."""
+    i = j = 0
+    tot = 0.0
+    while i < len(u1) and j < len(u2):
+        lo, hi = max(u1[i][0], u2[j][0]), min(u1[i][1], u2[j][1])
+        if hi > lo:
+            tot += hi - lo
+        if u1[i][1] < u2[j][1]:
+            i += 1
+        else:
+            j += 1
+    return tot
+
+
+def run_offload(spec, args):
+    """Stack with host-offloaded experts: one step = one speculative-decoding iteration on synthetic inputs.
+
+    Drafting stage: for each of the T-1 draft forward passes and each layer, the predictor (target gate on
+    the draft hidden state, Alg. 1) and the prefetcher (Alg. 2) run for layers <= cutoff, and a dense
+    SwiGLU FFN of the same d x f shape runs on the compute stream as a stand-in for the draft model's layer.
+    Verification stage: spmoe_moe_verify_layer on every layer for the T-token batch."""
+    import numpy as np
+    import torch
+    import spmoe_inputs as si
+    from paper_2510_10302_amd import workload as W
+
+    d, f, E, k, T, n_shared = spec["d"], spec["f"], spec["E"], spec["k"], spec["T"], spec["shared"]
+    layers = args.layers or spec["layers"]
+    pred_k = args.pred_k or k
+    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    t0 = time.time()
+    wl = W.Workload(d=d, f=f, E=E, k=k, shared=n_shared, dtype="bf16", layers=layers, seed=0,
+                    distinct=min(args.distinct, layers * E))
+    cfg = W.make_config(wl, max_tokens=T, slots=spec["slots"], cutoff_layer=args.cutoff, pred_k=pred_k)
+    L = W.Loaded(wl, cfg, warm=False, keep_canonical=False)
+    dwl = W.Workload(d=d, f=f, E=1, k=1, shared=0, dtype="bf16", layers=layers, seed=1, distinct=2)
+    D = W.Loaded(dwl, W.make_config(dwl, max_tokens=1), keep_canonical=False)
+    blob = W.sp.expert_blob_bytes(cfg)
+    log("bench: offload workload %s: %d layers, %d slots/layer, cutoff %d, sigma %.2f, pred_k %d, built in %.1f s"
+        % (args.workload, layers, spec["slots"], args.cutoff, args.sigma, pred_k, time.time() - t0))
+
+    # host link peak: one 1 GiB pinned -> device copy
+    pin = torch.empty(2 ** 30, dtype=torch.uint8, pin_memory=True)
+    dev = torch.empty(2 ** 30, dtype=torch.uint8, device="cuda")
+    dev.copy_(pin, non_blocking=True)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    dev.copy_(pin, non_blocking=True)
+    e1.record()
+    torch.cuda.synchronize()
+    link_gbs = 2 ** 30 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del pin, dev
+
+    n_it = warmup + steps
+    xs = [[torch.from_numpy(si.hidden(7, T, d, iteration=i, layer=l)).cuda() for l in range(layers)] for i in range(n_it)]
+    dxs = [[xs[i][l] + torch.from_numpy(si.draft_noise(7, T, d, args.sigma, iteration=i, layer=l)).cuda()
+            for l in range(layers)] for i in range(n_it)]
+    out = torch.empty((T, d), dtype=torch.float32, device="cuda")
+    dout = torch.empty((1, d), dtype=torch.float32, device="cuda")
+    ctx, dctx = L.ctx, D.ctx
+
+    def iteration(i):
+        for j in range(T - 1):
+            for l in range(layers):
+                if 0 <= l <= args.cutoff:
+                    ctx.prefetch(l, ctx.predict_experts(l, dxs[i][l][j:j + 1]))
+                dctx.moe_verify_layer(l, dxs[i][l][j:j + 1], dout)
+        for l in range(layers):
+            ctx.moe_verify_layer(l, xs[i][l], out)
+        ctx.sync()
+
+    for i in range(warmup):
+        iteration(i)
+    torch.cuda.synchronize()
+    st0 = ctx.expert_cache_stats()
+    t_start = time.perf_counter()
+    for i in range(warmup, n_it):
+        iteration(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    st1 = ctx.expert_cache_stats()
+    stats = {key: st1[key] - st0[key] for key in st1}
+
+    # profiled pass (events around every copy and every expert-GEMM launch) over a few more iterations
+    n_prof = min(3, steps)
+    ctx.profile_begin()
+    dctx.profile_begin()
+    for i in range(n_it - n_prof, n_it):
+        iteration(i)
+    recs = ctx.profile_collect(cap=200000) + dctx.profile_collect(cap=200000)
+    pre = union([(r["t0"], r["t1"]) for r in recs if r["kind"] == 1])
+    ond = union([(r["t0"], r["t1"]) for r in recs if r["kind"] == 2])
+    busy = union([(r["t0"], r["t1"]) for r in recs if r["kind"] == 4])
+    copy_ms = {"prefetch": measure(pre), "ondemand": measure(ond)}
+    hidden = {"prefetch": intersect(pre, busy), "ondemand": intersect(ond, busy)}
+    n_pre = sum(1 for r in recs if r["kind"] == 1)
+    n_ond = sum(1 for r in recs if r["kind"] == 2)
+    h2d_gbs = ((n_pre + n_ond) * blob / 1e9) / (max(measure(union(pre + ond)), 1e-9) * 1e-3)
+
+    ms_per_step = elapsed * 1e3 / steps
+    hits, misses = stats["hits"], stats["misses"]
+    result = {
+        "metric": "moe_verify_stack_tokens_per_s", "value": T * steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": layers, "d_model": d, "d_ff": f, "n_experts": E, "top_k": k,
+                   "n_shared": n_shared, "verify_tokens": T, "cache_slots_per_layer": spec["slots"], "cutoff_layer": args.cutoff,
+                   "draft_sigma": args.sigma, "pred_k": pred_k, "distinct_blobs": wl.distinct,
+                   "draft_stage": "T-1 passes of a dense d x f SwiGLU FFN per layer (stand-in)"},
+        "per_layer_verify_us_incl_stalls": ms_per_step * 1e3 / layers,
+        "hit_rate": hits / max(hits + misses, 1), "cache_stats": stats,
+        "h2d": {"link_peak_gbs_measured": link_gbs, "achieved_gbs_while_copying": h2d_gbs,
+                "prefetch_copy_ms": copy_ms["prefetch"], "ondemand_copy_ms": copy_ms["ondemand"],
+                "prefetch_hidden_frac": hidden["prefetch"] / max(copy_ms["prefetch"], 1e-9),
+                "ondemand_hidden_frac": hidden["ondemand"] / max(copy_ms["ondemand"], 1e-9),
+                "compute_busy_ms": measure(busy), "profiled_iterations": n_prof},
+        "roofline": {"bound": "host-link", "achieved": h2d_gbs, "peak": link_gbs, "unit": "GB/s",
+                     "frac": h2d_gbs / link_gbs, "traffic": None},
+    }
+    L.close()
+    D.close()
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +186,13 @@ def main():
     ap.add_argument("--workload", default="c2_mixtral_8x7b")
     ap.add_argument("--batches", type=int, default=20, help="distinct synthetic token batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--resident", action="store_true",
+                    help="time one layer of the workload's shape with every expert resident (compute-only number)")
+    ap.add_argument("--layers", type=int, default=0, help="offload workloads: number of layers (0 = the config's)")
+    ap.add_argument("--cutoff", type=int, default=4, help="offload workloads: cutoff layer L of the prefetcher (-1 = off)")
+    ap.add_argument("--sigma", type=float, default=0.1, help="offload workloads: draft-noise std")
+    ap.add_argument("--pred-k", type=int, default=0, help="offload workloads: k of the predictor (0 = top_k)")
+    ap.add_argument("--distinct", type=int, default=32, help="offload workloads: distinct expert blobs backing the stack")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
                     help="only run N plain 1 GiB device copies (counter calibration for rocprofv3 --pmc) and exit")
     args = ap.parse_args()
@@ -72,6 +220,9 @@ def main():
         print(json.dumps({"calibrate_copy": args.calibrate_copy, "bytes_read": 2 ** 30, "bytes_written": 2 ** 30}))
         return
     spec = dict(W.CONFIGS[args.workload])
+    if spec["slots"] and not args.resident:
+        run_offload(spec, args)
+        return
     d, f, E, k, T = spec["d"], spec["f"], spec["E"], spec["k"], spec["T"]
     n_shared = spec["shared"]
     # one layer, every expert resident: the compute-only verify layer at the real layer shape

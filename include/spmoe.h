@@ -84,7 +84,8 @@ typedef struct {
 
 /* One timed interval recorded while profiling is enabled (times in ms since spmoe_profile_begin). */
 typedef struct {
-    int32_t kind;      /* 0: verify-layer compute span, 1: prefetch copy, 2: on-demand copy, 3: predict */
+    int32_t kind;      /* 0: verify-layer span (first kernel launch to combine, waits included), 1: prefetch copy,
+                          2: on-demand copy, 3: predict, 4: one launch of the two expert GEMMs (kernels executing) */
     int32_t layer;
     int32_t expert;    /* copies: expert id; compute spans: number of experts launched */
     int32_t reserved;

@@ -201,9 +201,12 @@ void kernel_mark(spmoe_ctx* c, int i) {
 }
 
 // One launch of the two expert GEMMs for the experts in `list`, timed per kernel when profiling.
-spmoe_status launch_experts(spmoe_ctx* c, const SpmoeShape& sh, const SpmoeExpertList& list, const float* x) {
+spmoe_status launch_experts(spmoe_ctx* c, int layer, const SpmoeShape& sh, const SpmoeExpertList& list, const float* x) {
     if (list.n <= 0) return SPMOE_OK;
     TimedSpan k2{nullptr, nullptr, 1, 0, list.n}, k3{nullptr, nullptr, 2, 0, list.n};
+    size_t busy;
+    spmoe_status st = span_begin(c, c->compute, 4, layer, list.n, &busy);   // kernels really executing
+    if (st != SPMOE_OK) return st;
     if (c->profiling) {
         HIP_TRY(c, hipEventCreate(&k2.begin));
         HIP_TRY(c, hipEventCreate(&k2.end));
@@ -219,7 +222,7 @@ spmoe_status launch_experts(spmoe_ctx* c, const SpmoeShape& sh, const SpmoeExper
         c->kspans.push_back(k2);
         c->kspans.push_back(k3);
     }
-    return SPMOE_OK;
+    return span_end(c, c->compute, busy);
 }
 
 void free_kspans(spmoe_ctx* c) {
@@ -657,7 +660,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
             if (!copy_done(sl)) HIP_TRY(c, hipStreamWaitEvent(c->compute, sl.ready, 0));
             add(e, sl.dev);
         }
-        st = launch_experts(c, sh, list, dev_x);
+        st = launch_experts(c, layer, sh, list, dev_x);
         if (st != SPMOE_OK) return st;
     } else {
         // offloaded experts: the per-expert token counts decide which experts this batch needs
@@ -690,7 +693,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
         });
         for (int s = 0; s < c->cfg.n_shared; ++s) add(E + s, L.shared_dev[s]);
         for (int e : landed) add(e, L.slots[L.slot_of[e]].dev);
-        st = launch_experts(c, sh, list, dev_x);
+        st = launch_experts(c, layer, sh, list, dev_x);
         if (st != SPMOE_OK) return st;
         for (int e : landed) {
             Slot& sl = L.slots[L.slot_of[e]];
@@ -702,7 +705,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
             HIP_TRY(c, hipStreamWaitEvent(c->compute, sl.ready, 0));
             list.n = 0;
             add(e, sl.dev);
-            spmoe_status s2 = launch_experts(c, sh, list, dev_x);
+            spmoe_status s2 = launch_experts(c, layer, sh, list, dev_x);
             if (s2 != SPMOE_OK) return s2;
             HIP_TRY(c, hipEventRecord(sl.freed, c->compute));
             sl.freed_valid = true;

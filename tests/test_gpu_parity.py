@@ -164,3 +164,50 @@ def test_gate_topk_many_tokens_bit_exact(oracle32):
         print("gate_topk", (E, k, d), "exact", exact, "near-ties", near_total)
         assert exact >= 6 * 32 - 2
         L.close()
+
+
+def test_c4_deepseek_layer_full_size(oracle32):
+    # BASELINE config 4 layer shape: d=2048, f=1408, 64 routed experts top-6 + 2 shared, bf16, 16 tokens
+    wl = _wl(d=2048, f=1408, E=64, k=6, shared=2, dtype="bf16", layers=1, seed=0)
+    L = _loaded(wl, 16)
+    for it in range(2):
+        x = si.hidden(40, 16, 2048, iteration=it)
+        rep = check_layer(gpu_layer(L, 0, x), oracle_layer(oracle32, wl, 0, x), 6, REL_L2_BF16)
+        print("c4", rep)
+    L.close()
+
+
+def test_c5_mixtral_8x22b_layer_full_size(oracle32):
+    # BASELINE config 5 layer shape: d=6144, f=16384, 8 experts top-2, bf16, 32 tokens (4 sequences x 8)
+    wl = _wl(d=6144, f=16384, E=8, k=2, shared=0, dtype="bf16", layers=1, seed=0)
+    L = _loaded(wl, 32)
+    x = si.hidden(50, 32, 6144)
+    g = gpu_layer(L, 0, x)
+    ref = oracle_layer(oracle32, wl, 0, x)
+    rep = check_layer(g, ref, 2, REL_L2_BF16)
+    print("c5", rep, "tokens per expert", np.bincount(ref["idx"].reshape(-1), minlength=8).tolist())
+    L.close()
+
+
+def test_c3_offloaded_stack_teacher_forced(oracle32):
+    # BASELINE config 3 (reduced to 3 layers, aliased backing): Mixtral-8x7B layers, experts in pinned host
+    # memory, 3 cache slots per layer, draft noise sigma 0.5, cutoff layer 1; each layer is fed seeded x_l.
+    import torch
+    from paper_2510_10302_amd import workload as W
+    wl = W.Workload(d=4096, f=14336, E=8, k=2, shared=0, dtype="bf16", layers=3, seed=0, distinct=8)
+    L = W.Loaded(wl, W.make_config(wl, max_tokens=8, slots=3, cutoff_layer=1, pred_k=2), warm=False)
+    for it in range(2):
+        xs = [si.hidden(60, 8, 4096, iteration=it, layer=l) for l in range(3)]
+        for l in range(3):
+            for j in range(7):
+                dx = xs[l][j:j + 1] + si.draft_noise(60, 1, 4096, 0.5, iteration=it * 8 + j, layer=l)
+                L.ctx.prefetch(l, L.ctx.predict_experts(l, torch.from_numpy(dx).cuda()))
+        for l in range(3):
+            g = gpu_layer(L, l, xs[l])
+            ref = oracle_layer(oracle32, wl, l, xs[l])
+            rep = check_layer(g, ref, 2, REL_L2_BF16)
+            print("c3 it", it, "layer", l, rep)
+    st = L.ctx.expert_cache_stats()
+    print("c3 stats", st)
+    assert st["prefetch_issued"] > 0 and st["misses"] > 0 and st["hits"] > 0
+    L.close()

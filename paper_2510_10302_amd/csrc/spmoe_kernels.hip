@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
+#include <stdlib.h>
 
 #include "spmoe_internal.h"
 
@@ -275,13 +276,18 @@ __global__ __launch_bounds__(256) void permute_kernel(const int32_t* idx, int T,
 }
 
 // ---------------------------------------------------------------------------------------------
-// K2 / K3: grouped skinny GEMM on MFMA.
+// K2 / K3: grouped skinny GEMM on MFMA, persistent workgroups.
 //
-// One workgroup = (one expert of the launch's list, one tile of <= 16 of its tokens, one N-tile of
-// 16 weight rows, one K-split).  Its W waves split the K range; wave w streams KSW k-steps (1 KiB
-// per matrix per k-step) with a register ring of PF steps, multiplies each 16x32 weight tile with
-// the 32x16 token tile it keeps in registers for its K range, and the W partial 16x16 results are
-// summed through LDS in wave order (deterministic).
+// Work unit = (group, K-split, N-tile): a group is one expert of the launch's list together with a
+// tile of <= 16 of its tokens; an N-tile is 16 weight rows.  All units of a launch are numbered
+// group-major and cut into gridDim.x equal contiguous ranges, one per workgroup, so every workgroup
+// streams the same number of weight bytes whatever the routing was.
+//
+// Inside a workgroup the W waves split the K range of a unit (KSW k-steps each, 1 KiB per matrix per
+// k-step).  A wave keeps its slice of the token tile as the MFMA B operand in registers (reloaded only
+// when the group or K-split changes), streams weight tiles from HBM through a register ring of PF
+// k-steps that runs across unit boundaries, and the W partial 16x16 results of a unit are summed
+// through a double-buffered LDS area in wave order (deterministic), one barrier per unit.
 //
 // MODE_GU   : A = interleaved W_gate / W_up tiles, B = x rows gathered through perm (fp32 -> bf16 on
 //             load); epilogue h[a][n] = silu(g) * u stored as bf16.
@@ -289,8 +295,12 @@ __global__ __launch_bounds__(256) void permute_kernel(const int32_t* idx, int T,
 //
 // MFMA 16x16x32 operand layout used here: A lane l = row (l & 15), K = 8*(l >> 4) .. +7; B lane l =
 // column (l & 15), same K; D lane l = column (l & 15), rows 4*(l >> 4) .. +3.
+//
+// The MFMA chain is branch-free: k-steps past the end of a ragged K range run with zero operands.
 // ---------------------------------------------------------------------------------------------
 enum { MODE_GU = 0, MODE_DOWN = 1 };
+
+#define GEMM_MAX_GROUPS (2 * SPMOE_MAX_ETOT)
 
 struct GemmParams {
     const int32_t* offsets;
@@ -301,124 +311,197 @@ struct GemmParams {
     int32_t T, k, d, f;
     int32_t A_tot;        // T*k + n_shared*T
     int32_t ks_total;     // k-steps of the contraction: d/32 (GU), f/32 (DOWN)
-    int32_t ks_split;     // k-steps per K-split (gridDim.z splits)
-    int32_t mt_tiles;     // token tiles per expert covered by gridDim.y (1 or 2)
+    int32_t ks_split;     // k-steps per K-split
+    int32_t splits;       // K-splits
+    int32_t n_tiles;      // N-tiles: f/16 (GU), d/16 (DOWN)
     int32_t waves;        // waves per workgroup
 };
 
-template <int MODE, int KSW, bool EXACT, int PF>
-__global__ __launch_bounds__((KSW > 16 ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list, const GemmParams p) {
-    constexpr int NMAT = (MODE == MODE_GU) ? 2 : 1;
-    extern __shared__ float s_red[];   // [waves][NMAT][64 lanes][4]
+// largest divisor of ksw that is <= limit (the ring must divide the per-unit step count so that ring
+// slots keep static register indices across units)
+constexpr int ring_depth(int ksw, int limit) {
+    int best = 1;
+    for (int v = 1; v <= limit; ++v)
+        if (ksw % v == 0) best = v;
+    return best;
+}
 
-    const int li = blockIdx.y / p.mt_tiles;
-    const int mt = blockIdx.y - li * p.mt_tiles;
-    const int e = list.id[li];
-    const int beg = p.offsets[e] + 16 * mt;
-    const int cnt = min(16, p.offsets[e + 1] - beg);
-    if (cnt <= 0) return;                              // uniform over the workgroup
+template <int MODE, int KSW, bool EXACT>
+__global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list,
+                                                                                const GemmParams p) {
+    constexpr int NMAT = (MODE == MODE_GU) ? 2 : 1;
+    constexpr int PF = ring_depth(KSW, MODE == MODE_GU ? 4 : 8);
+    constexpr int STEP = NMAT * 64;                       // 16-byte units per k-step of one N-tile
+    extern __shared__ float s_mem[];
+    float* s_red = s_mem;                                 // [2][waves][NMAT][64 lanes][4]
+    int* s_grp = reinterpret_cast<int*>(s_mem + 2 * p.waves * NMAT * 256);   // [GEMM_MAX_GROUPS + 1]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kg = lane >> 4;
-    const int nt = blockIdx.x;
-    const int K = (MODE == MODE_GU) ? p.d : p.f;       // contraction length
-    const int N = (MODE == MODE_GU) ? p.f : p.d;       // output features
+    const int K = (MODE == MODE_GU) ? p.d : p.f;          // contraction length
+    const int N = (MODE == MODE_GU) ? p.f : p.d;          // output features
 
-    // this wave's k-step range inside the split
-    const int ks_lo = blockIdx.z * p.ks_split + wave * KSW;
-    const int ks_hi = min(min(ks_lo + KSW, (int)(blockIdx.z + 1) * p.ks_split), p.ks_total);
-    // number of k-steps this wave really has: KSW for an exact plan, fewer (wave-uniform) otherwise.
-    // Steps beyond nks run with all-zero operands, so the MFMA chain below has no branches.
-    const int nks = EXACT ? KSW : __builtin_amdgcn_readfirstlane(max(ks_hi - ks_lo, 0));
+    // ---- active groups of this launch: (list entry, token tile) pairs with at least one token
+    if (wave == 0) {
+        int base = 0;
+        for (int i0 = 0; i0 < list.n; i0 += 64) {
+            const int i = i0 + lane;
+            int tiles = 0;
+            if (i < list.n) {
+                const int e = list.id[i];
+                tiles = (p.offsets[e + 1] - p.offsets[e] + 15) >> 4;
+            }
+            int incl = tiles;                             // inclusive scan over the wave
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int v = __shfl_up(incl, off);
+                if (lane >= off) incl += v;
+            }
+            const int excl = incl - tiles;
+            for (int t = 0; t < tiles; ++t) s_grp[base + excl + t] = i * 2 + t;
+            base += __shfl(incl, 63);
+        }
+        if (lane == 0) s_grp[GEMM_MAX_GROUPS] = base;
+    }
+    __syncthreads();
+    const int n_groups = s_grp[GEMM_MAX_GROUPS];
+    const int upg = p.splits * p.n_tiles;                 // units per group
+    const long long U = (long long)n_groups * upg;
+    const int u0 = (int)(U * blockIdx.x / gridDim.x), u1 = (int)(U * (blockIdx.x + 1) / gridDim.x);
+    if (u0 >= u1) return;                                 // uniform over the workgroup
 
-    // weight stream of this wave: tile (nt, ks) of matrix m sits at ((nt*ks_total + ks)*NMAT + m) KiB
-    const char* blob = static_cast<const char*>(list.blob[li]);
-    if (MODE == MODE_DOWN) blob += (size_t)2 * p.d * p.f * sizeof(uint16_t);
-    const bf16x8* wp = reinterpret_cast<const bf16x8*>(blob) + ((size_t)nt * p.ks_total + ks_lo) * (NMAT * 64) + lane;
     const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+    const size_t region = (MODE == MODE_DOWN) ? (size_t)2 * p.d * p.f * sizeof(uint16_t) : 0;
 
+    // weight stream address of unit u for this wave (16-byte units), and its live k-step count
+    auto unit_ptr = [&](int u, int& nks) -> const bf16x8* {
+        const int g = u / upg, rem = u - g * upg;
+        const int s = rem / p.n_tiles, nt = rem - s * p.n_tiles;
+        const int li = s_grp[g] >> 1;
+        const int ks_lo = s * p.ks_split + wave * KSW;
+        const int ks_hi = min(min(ks_lo + KSW, (s + 1) * p.ks_split), p.ks_total);
+        nks = EXACT ? KSW : max(ks_hi - ks_lo, 0);
+        const char* blob = static_cast<const char*>(list.blob[li]) + region;
+        return reinterpret_cast<const bf16x8*>(blob) + ((size_t)nt * p.ks_total + ks_lo) * STEP + lane;
+    };
+
+    int nks = KSW;
+    const bf16x8* wp = unit_ptr(u0, nks);
     bf16x8 ring[PF][NMAT];
 #pragma unroll
     for (int j = 0; j < PF; ++j) {
 #pragma unroll
         for (int m = 0; m < NMAT; ++m) {
             ring[j][m] = zero8;
-            if (j < KSW && (EXACT || j < nks)) ring[j][m] = __builtin_nontemporal_load(wp + (size_t)j * (NMAT * 64) + m * 64);
+            if (EXACT || j < nks) ring[j][m] = __builtin_nontemporal_load(wp + (size_t)j * STEP + m * 64);
         }
     }
 
-    // token tile (B operand) for this wave's K range, kept in registers
-    const int a_n = (n < cnt) ? p.perm[beg + n] : -1;
     bf16x8 xr[KSW];
-    if (MODE == MODE_GU) {
-        const int routed = p.T * p.k;
-        const int tok = (a_n < 0) ? 0 : (a_n < routed ? a_n / p.k : (a_n - routed) % p.T);
-        const float* xrow = p.x + (size_t)tok * K + ks_lo * 32 + kg * 8;
+    int cur_gs = -1;                                      // group * splits + split held in xr
+    int beg = 0, cnt = 0;
+    int a_out = -1;                                       // assignment this thread writes in the epilogue
+    int buf = 0;
+
+    for (int u = u0; u < u1; ++u) {
+        const int g = u / upg, rem = u - g * upg;
+        const int s = rem / p.n_tiles, nt = rem - s * p.n_tiles;
+
+        // ---- token tile (B operand) of this wave's K range; reloaded when the group or split changes
+        if (g * p.splits + s != cur_gs) {
+            cur_gs = g * p.splits + s;
+            const int gi = s_grp[g];
+            const int e = list.id[gi >> 1];
+            beg = p.offsets[e] + 16 * (gi & 1);
+            cnt = min(16, p.offsets[e + 1] - beg);
+            const int ks_lo = s * p.ks_split + wave * KSW;
+            const int a_n = (n < cnt) ? p.perm[beg + n] : -1;
+            a_out = (tid < 256 && (tid >> 4) < cnt) ? p.perm[beg + (tid >> 4)] : -1;
+            if (MODE == MODE_GU) {
+                const int routed = p.T * p.k;
+                const int tok = (a_n < 0) ? 0 : (a_n < routed ? a_n / p.k : (a_n - routed) % p.T);
+                const float* xrow = p.x + (size_t)tok * K + ks_lo * 32 + kg * 8;
+#pragma unroll
+                for (int j = 0; j < KSW; ++j) {
+                    u32x4 packed = {0u, 0u, 0u, 0u};
+                    if (a_n >= 0 && (EXACT || j < nks)) {
+                        const float4 lo = *reinterpret_cast<const float4*>(xrow + j * 32);
+                        const float4 hi = *reinterpret_cast<const float4*>(xrow + j * 32 + 4);
+                        packed[0] = pack_bf16x2(lo.x, lo.y); packed[1] = pack_bf16x2(lo.z, lo.w);
+                        packed[2] = pack_bf16x2(hi.x, hi.y); packed[3] = pack_bf16x2(hi.z, hi.w);
+                    }
+                    xr[j] = __builtin_bit_cast(bf16x8, packed);
+                }
+            } else {
+                const uint16_t* hrow = p.h + (size_t)max(a_n, 0) * K + ks_lo * 32 + kg * 8;
+#pragma unroll
+                for (int j = 0; j < KSW; ++j) {
+                    u32x4 packed = {0u, 0u, 0u, 0u};
+                    if (a_n >= 0 && (EXACT || j < nks)) packed = *reinterpret_cast<const u32x4*>(hrow + j * 32);
+                    xr[j] = __builtin_bit_cast(bf16x8, packed);
+                }
+            }
+        }
+
+        // ---- stream the unit's KSW k-steps; the ring refills from this unit, then from the next one
+        int nks_next = 0;
+        const bf16x8* wp_next = (u + 1 < u1) ? unit_ptr(u + 1, nks_next) : nullptr;
+        f32x4 acc[NMAT];
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < KSW; ++j) {
-            u32x4 packed = {0u, 0u, 0u, 0u};
-            if (a_n >= 0 && (EXACT || j < nks)) {
-                const float4 lo = *reinterpret_cast<const float4*>(xrow + j * 32);
-                const float4 hi = *reinterpret_cast<const float4*>(xrow + j * 32 + 4);
-                packed[0] = pack_bf16x2(lo.x, lo.y); packed[1] = pack_bf16x2(lo.z, lo.w);
-                packed[2] = pack_bf16x2(hi.x, hi.y); packed[3] = pack_bf16x2(hi.z, hi.w);
+            bf16x8 a[NMAT];
+#pragma unroll
+            for (int m = 0; m < NMAT; ++m) a[m] = ring[j % PF][m];
+            if (j + PF < KSW) {
+#pragma unroll
+                for (int m = 0; m < NMAT; ++m) {
+                    ring[j % PF][m] = zero8;
+                    if (EXACT || j + PF < nks)
+                        ring[j % PF][m] = __builtin_nontemporal_load(wp + (size_t)(j + PF) * STEP + m * 64);
+                }
+            } else {
+#pragma unroll
+                for (int m = 0; m < NMAT; ++m) {
+                    ring[j % PF][m] = zero8;
+                    if (wp_next != nullptr && (EXACT || j + PF - KSW < nks_next))
+                        ring[j % PF][m] = __builtin_nontemporal_load(wp_next + (size_t)(j + PF - KSW) * STEP + m * 64);
+                }
             }
-            xr[j] = __builtin_bit_cast(bf16x8, packed);
+#pragma unroll
+            for (int m = 0; m < NMAT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], xr[j], acc[m], 0, 0, 0);
         }
-    } else {
-        const uint16_t* hrow = p.h + (size_t)max(a_n, 0) * K + ks_lo * 32 + kg * 8;
-#pragma unroll
-        for (int j = 0; j < KSW; ++j) {
-            u32x4 packed = {0u, 0u, 0u, 0u};
-            if (a_n >= 0 && (EXACT || j < nks)) packed = *reinterpret_cast<const u32x4*>(hrow + j * 32);
-            xr[j] = __builtin_bit_cast(bf16x8, packed);
-        }
-    }
+        wp = wp_next;
+        nks = nks_next;
 
-    f32x4 acc[NMAT];
+        // ---- cross-wave reduction through LDS (buffer `buf`), summed in wave order
+        float* red = s_red + buf * (p.waves * NMAT * 256);
 #pragma unroll
-    for (int m = 0; m < NMAT; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-#pragma unroll
-    for (int j = 0; j < KSW; ++j) {
-        bf16x8 a[NMAT];
-#pragma unroll
-        for (int m = 0; m < NMAT; ++m) a[m] = ring[j % PF][m];
-        if (j + PF < KSW) {
-#pragma unroll
-            for (int m = 0; m < NMAT; ++m) {
-                ring[j % PF][m] = zero8;
-                if (EXACT || j + PF < nks)
-                    ring[j % PF][m] = __builtin_nontemporal_load(wp + (size_t)(j + PF) * (NMAT * 64) + m * 64);
+        for (int m = 0; m < NMAT; ++m) *reinterpret_cast<f32x4*>(red + ((wave * NMAT + m) * 64 + lane) * 4) = acc[m];
+        // LDS writes done, then workgroup barrier; outstanding weight loads keep flying across it
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        // o -> (token on, feature fi), consecutive threads on consecutive features; workgroups of fewer
+        // than four waves take several outputs per thread
+        for (int o = tid; o < 256; o += blockDim.x) {
+            const int fi = o & 15, on = o >> 4;
+            if (on >= cnt) break;
+            const int a_o = (o == tid) ? a_out : p.perm[beg + on];
+            const int src = (((fi >> 2) * 16 + on) * 4) + (fi & 3);
+            float s0 = 0.f, s1 = 0.f;
+            for (int w = 0; w < p.waves; ++w) {
+                s0 += red[(w * NMAT) * 256 + src];
+                if (NMAT == 2) s1 += red[(w * NMAT + 1) * 256 + src];
+            }
+            const int feat = nt * 16 + fi;
+            if (MODE == MODE_GU) {
+                const float hval = (s0 / (1.f + expf(-s0))) * s1;
+                p.h[(size_t)a_o * N + feat] = (uint16_t)f32_to_bf16_bits(hval);
+            } else {
+                p.ypart[((size_t)s * p.A_tot + a_o) * N + feat] = s0;
             }
         }
-#pragma unroll
-        for (int m = 0; m < NMAT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], xr[j], acc[m], 0, 0, 0);
-    }
-
-    // cross-wave reduction through LDS, summed in wave order
-#pragma unroll
-    for (int m = 0; m < NMAT; ++m)
-        *reinterpret_cast<f32x4*>(s_red + ((wave * NMAT + m) * 64 + lane) * 4) = acc[m];
-    __syncthreads();
-    for (int o = tid; o < 256; o += blockDim.x) {
-        // o -> (token on, feature fi) with consecutive threads on consecutive features
-        const int fi = o & 15, on = o >> 4;
-        if (on >= cnt) continue;
-        const int src = (((fi >> 2) * 16 + on) * 4) + (fi & 3);
-        float s0 = 0.f, s1 = 0.f;
-        for (int w = 0; w < p.waves; ++w) {
-            s0 += s_red[(w * NMAT) * 256 + src];
-            if (NMAT == 2) s1 += s_red[(w * NMAT + 1) * 256 + src];
-        }
-        const int a_o = p.perm[beg + on];
-        const int feat = nt * 16 + fi;
-        if (MODE == MODE_GU) {
-            const float hval = (s0 / (1.f + expf(-s0))) * s1;
-            p.h[(size_t)a_o * N + feat] = (uint16_t)f32_to_bf16_bits(hval);
-        } else {
-            p.ypart[((size_t)blockIdx.z * p.A_tot + a_o) * N + feat] = s0;
-        }
+        buf ^= 1;
     }
 }
 
@@ -553,10 +636,18 @@ static bool is_exact_ksw(int ksw) {
     return false;
 }
 
-// Workgroups of more than 8 waves leave 128 VGPRs per lane, enough for 16 k-steps of token tile.
-static bool plan_ok(int waves, int ksw) { return ksw <= 16 || waves <= 8; }
+// Workgroups of more than 8 waves leave 128 VGPRs per lane, enough for 12 k-steps of token tile.
+static bool plan_ok(int waves, int ksw) { return ksw <= 12 || waves <= 8; }
 
 static GemmPlan plan_gemm(int ks_total, int max_splits) {
+    const char* force = getenv("SPMOE_GEMM_WAVES");   // tuning aid: preferred waves per workgroup
+    const int forced = force ? atoi(force) : 0;
+    if (forced > 0)
+        for (int splits = 1; splits <= max_splits; splits *= 2) {
+            if (ks_total % (splits * forced)) continue;
+            const int ksw = ks_total / splits / forced;
+            if (is_exact_ksw(ksw) && plan_ok(forced, ksw)) return GemmPlan{splits, forced, ksw, true};
+        }
     for (int splits = 1; splits <= max_splits; splits *= 2) {
         if (ks_total % splits) break;
         const int per = ks_total / splits;
@@ -579,24 +670,48 @@ int spmoe_down_splits(int dtype, int d, int f) {
     return plan_gemm(f / 32, 4).splits;
 }
 
+// Persistent grid size: as many workgroups as fit on the chip at once for this instance.
+template <typename Kernel>
+static int resident_blocks(Kernel kernel, int threads, size_t lds) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, lds) != hipSuccess || per_cu <= 0) {
+        (void)hipGetLastError();
+        per_cu = 1;
+    }
+    return cus * per_cu;
+}
+
 template <int MODE>
-static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, dim3 grid, const SpmoeExpertList& list,
+static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, const SpmoeExpertList& list,
                                    const GemmParams& p) {
-    const dim3 block(plan.waves * 64);
-    const size_t lds = (size_t)plan.waves * (MODE == MODE_GU ? 2 : 1) * 256 * sizeof(float);
-    constexpr int PF = (MODE == MODE_GU) ? 4 : 8;
-#define SPMOE_GEMM_CASE(KSW_)                                                                                   \
-    case KSW_:                                                                                                  \
-        hipLaunchKernelGGL((expert_gemm_kernel<MODE, KSW_, true, PF>), grid, block, lds, stream, list, p);      \
-        break;
+    const int threads = plan.waves * 64;
+    const size_t lds = (size_t)2 * plan.waves * (MODE == MODE_GU ? 2 : 1) * 256 * sizeof(float) +
+                       (GEMM_MAX_GROUPS + 1) * sizeof(int);
+    // cache of grid sizes per (instance, waves): [exact ksw index or generic][waves]
+    static int grid_cache[2][16][17];
+#define SPMOE_GEMM_CASE(SLOT_, KSW_, EXACT_)                                                                    \
+    {                                                                                                           \
+        int& g = grid_cache[MODE][SLOT_][plan.waves];                                                           \
+        if (g == 0) g = resident_blocks(expert_gemm_kernel<MODE, KSW_, EXACT_>, threads, lds);                  \
+        hipLaunchKernelGGL((expert_gemm_kernel<MODE, KSW_, EXACT_>), dim3(g), dim3(threads), lds, stream, list, p); \
+    }
     if (plan.exact) {
         switch (plan.ksw) {
-            SPMOE_GEMM_CASE(32) SPMOE_GEMM_CASE(28) SPMOE_GEMM_CASE(24) SPMOE_GEMM_CASE(16) SPMOE_GEMM_CASE(14)
-            SPMOE_GEMM_CASE(12) SPMOE_GEMM_CASE(11) SPMOE_GEMM_CASE(8) SPMOE_GEMM_CASE(4)
+            case 32: SPMOE_GEMM_CASE(0, 32, true) break;
+            case 28: SPMOE_GEMM_CASE(1, 28, true) break;
+            case 24: SPMOE_GEMM_CASE(2, 24, true) break;
+            case 16: SPMOE_GEMM_CASE(3, 16, true) break;
+            case 14: SPMOE_GEMM_CASE(4, 14, true) break;
+            case 12: SPMOE_GEMM_CASE(5, 12, true) break;
+            case 11: SPMOE_GEMM_CASE(6, 11, true) break;
+            case 8: SPMOE_GEMM_CASE(7, 8, true) break;
+            case 4: SPMOE_GEMM_CASE(8, 4, true) break;
             default: return hipErrorInvalidValue;
         }
     } else {
-        hipLaunchKernelGGL((expert_gemm_kernel<MODE, 32, false, PF>), grid, block, lds, stream, list, p);
+        SPMOE_GEMM_CASE(9, 32, false)
     }
 #undef SPMOE_GEMM_CASE
     return hipGetLastError();
@@ -611,8 +726,7 @@ static GemmParams make_params(const SpmoeShape& s, const SpmoeRouting& r) {
     p.ypart = nullptr;
     p.T = s.T; p.k = s.k; p.d = s.d; p.f = s.f;
     p.A_tot = s.T * s.k + s.n_shared * s.T;
-    p.ks_total = 0; p.ks_split = 0;
-    p.mt_tiles = (s.T > 16) ? 2 : 1;
+    p.ks_total = 0; p.ks_split = 0; p.splits = 1; p.n_tiles = 0;
     p.waves = 4;
     return p;
 }
@@ -627,8 +741,10 @@ hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape&
         const GemmPlan plan = plan_gemm(s.d / 32, 1);
         p.ks_total = s.d / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
+        p.splits = plan.splits;
+        p.n_tiles = s.f / 16;
         p.waves = plan.waves;
-        return launch_gemm_bf16<MODE_GU>(stream, plan, dim3(s.f / 16, list.n * p.mt_tiles, 1), list, p);
+        return launch_gemm_bf16<MODE_GU>(stream, plan, list, p);
     }
     hipLaunchKernelGGL(expert_gemm_f32_kernel<MODE_GU>, dim3((s.f + 3) / 4, list.n), dim3(256), 0, stream, list, p,
                        static_cast<float*>(h));
@@ -646,8 +762,10 @@ hipError_t spmoe_launch_down(hipStream_t stream, int dtype, const SpmoeShape& s,
         if (plan.splits != splits) return hipErrorInvalidValue;
         p.ks_total = s.f / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
+        p.splits = plan.splits;
+        p.n_tiles = s.d / 16;
         p.waves = plan.waves;
-        return launch_gemm_bf16<MODE_DOWN>(stream, plan, dim3(s.d / 16, list.n * p.mt_tiles, plan.splits), list, p);
+        return launch_gemm_bf16<MODE_DOWN>(stream, plan, list, p);
     }
     hipLaunchKernelGGL(expert_gemm_f32_kernel<MODE_DOWN>, dim3((s.d + 3) / 4, list.n), dim3(256), 0, stream, list, p,
                        static_cast<float*>(const_cast<void*>(h)));

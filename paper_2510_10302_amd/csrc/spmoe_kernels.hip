@@ -169,22 +169,36 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* xt = x + (size_t)t * d;
 
-    // ---- gate logits: wave `wave` scores experts wave, wave+4, ...; lanes split d in chunks of 8
-    for (int e = wave; e < E; e += 4) {
-        const WT* we = wg + (size_t)e * d;
-        float acc = 0.f;
+    // ---- gate logits: each wave scores `epw` experts per pass (their loads are issued together, which
+    //      hides most of the memory latency); lanes split d in chunks of 8 elements
+    const int epw = (E >= 16) ? 4 : (E >= 8 ? 2 : 1);
+    for (int e0 = wave * epw; e0 < E; e0 += 4 * epw) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
         for (int j = lane * 8; j < d; j += 64 * 8) {
-            float wv[8];
-            load8_weights<WT>(we + j, wv);
             const float4 xa = *reinterpret_cast<const float4*>(xt + j);
             const float4 xb = *reinterpret_cast<const float4*>(xt + j + 4);
-            acc = fmaf(xa.x, wv[0], acc); acc = fmaf(xa.y, wv[1], acc);
-            acc = fmaf(xa.z, wv[2], acc); acc = fmaf(xa.w, wv[3], acc);
-            acc = fmaf(xb.x, wv[4], acc); acc = fmaf(xb.y, wv[5], acc);
-            acc = fmaf(xb.z, wv[6], acc); acc = fmaf(xb.w, wv[7], acc);
+            float wv[4][8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q < epw && e0 + q < E) load8_weights<WT>(wg + (size_t)(e0 + q) * d + j, wv[q]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (q < epw && e0 + q < E) {
+                    float a = acc[q];
+                    a = fmaf(xa.x, wv[q][0], a); a = fmaf(xa.y, wv[q][1], a);
+                    a = fmaf(xa.z, wv[q][2], a); a = fmaf(xa.w, wv[q][3], a);
+                    a = fmaf(xb.x, wv[q][4], a); a = fmaf(xb.y, wv[q][5], a);
+                    a = fmaf(xb.z, wv[q][6], a); a = fmaf(xb.w, wv[q][7], a);
+                    acc[q] = a;
+                }
         }
-        acc = wave_sum(acc);
-        if (lane == 0) s_logit[e] = acc;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (q < epw && e0 + q < E) {
+                const float sum = wave_sum(acc[q]);
+                if (lane == 0) s_logit[e0 + q] = sum;
+            }
     }
     __syncthreads();
 
@@ -290,8 +304,9 @@ __global__ __launch_bounds__(256) void permute_kernel(const int32_t* idx, int T,
 // through a double-buffered LDS area in wave order (deterministic), one barrier per unit.
 //
 // MODE_GU   : A = interleaved W_gate / W_up tiles, B = x rows gathered through perm (fp32 -> bf16 on
-//             load); epilogue h[a][n] = silu(g) * u stored as bf16.
-// MODE_DOWN : A = W_down tiles, B = h rows (bf16); epilogue ypart[split][a][n] = partial y (fp32).
+//             load); epilogue h[a][n] = silu(g) * u stored as bf16.  A unit covers one N-tile.
+// MODE_DOWN : A = W_down tiles of two consecutive N-tiles, B = h rows (bf16); epilogue
+//             ypart[split][a][n] = partial y (fp32).  A unit covers 32 weight rows.
 //
 // MFMA 16x16x32 operand layout used here: A lane l = row (l & 15), K = 8*(l >> 4) .. +7; B lane l =
 // column (l & 15), same K; D lane l = column (l & 15), rows 4*(l >> 4) .. +3.
@@ -313,7 +328,7 @@ struct GemmParams {
     int32_t ks_total;     // k-steps of the contraction: d/32 (GU), f/32 (DOWN)
     int32_t ks_split;     // k-steps per K-split
     int32_t splits;       // K-splits
-    int32_t n_tiles;      // N-tiles: f/16 (GU), d/16 (DOWN)
+    int32_t n_tiles;      // units along N: f/16 (GU), d/32 (DOWN)
     int32_t waves;        // waves per workgroup
 };
 
@@ -329,9 +344,12 @@ constexpr int ring_depth(int ksw, int limit) {
 template <int MODE, int KSW, bool EXACT>
 __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list,
                                                                                 const GemmParams p) {
-    constexpr int NMAT = (MODE == MODE_GU) ? 2 : 1;
-    constexpr int PF = ring_depth(KSW, MODE == MODE_GU ? 4 : 8);
-    constexpr int STEP = NMAT * 64;                       // 16-byte units per k-step of one N-tile
+    // Two weight tiles are in flight per k-step: gate and up tile of one N-tile (adjacent KiB) in MODE_GU,
+    // the tiles of two consecutive N-tiles in MODE_DOWN (ks_total KiB apart); both share the B operand.
+    constexpr int NMAT = 2;
+    constexpr int PF = ring_depth(KSW, 4);
+    constexpr int STEP = (MODE == MODE_GU) ? 128 : 64;    // 16-byte units between consecutive k-steps of a stream
+    const size_t soff = (MODE == MODE_GU) ? 64 : (size_t)p.ks_total * 64;   // second stream's offset
     extern __shared__ float s_mem[];
     float* s_red = s_mem;                                 // [2][waves][NMAT][64 lanes][4]
     int* s_grp = reinterpret_cast<int*>(s_mem + 2 * p.waves * NMAT * 256);   // [GEMM_MAX_GROUPS + 1]
@@ -382,7 +400,8 @@ __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(c
         const int ks_hi = min(min(ks_lo + KSW, (s + 1) * p.ks_split), p.ks_total);
         nks = EXACT ? KSW : max(ks_hi - ks_lo, 0);
         const char* blob = static_cast<const char*>(list.blob[li]) + region;
-        return reinterpret_cast<const bf16x8*>(blob) + ((size_t)nt * p.ks_total + ks_lo) * STEP + lane;
+        const size_t tile = (MODE == MODE_GU) ? (size_t)nt : (size_t)2 * nt;   // first tile of the unit
+        return reinterpret_cast<const bf16x8*>(blob) + (tile * p.ks_total + ks_lo) * STEP + lane;
     };
 
     int nks = KSW;
@@ -393,7 +412,7 @@ __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(c
 #pragma unroll
         for (int m = 0; m < NMAT; ++m) {
             ring[j][m] = zero8;
-            if (EXACT || j < nks) ring[j][m] = __builtin_nontemporal_load(wp + (size_t)j * STEP + m * 64);
+            if (EXACT || j < nks) ring[j][m] = __builtin_nontemporal_load(wp + (size_t)j * STEP + m * soff);
         }
     }
 
@@ -459,14 +478,14 @@ __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(c
                 for (int m = 0; m < NMAT; ++m) {
                     ring[j % PF][m] = zero8;
                     if (EXACT || j + PF < nks)
-                        ring[j % PF][m] = __builtin_nontemporal_load(wp + (size_t)(j + PF) * STEP + m * 64);
+                        ring[j % PF][m] = __builtin_nontemporal_load(wp + (size_t)(j + PF) * STEP + m * soff);
                 }
             } else {
 #pragma unroll
                 for (int m = 0; m < NMAT; ++m) {
                     ring[j % PF][m] = zero8;
                     if (wp_next != nullptr && (EXACT || j + PF - KSW < nks_next))
-                        ring[j % PF][m] = __builtin_nontemporal_load(wp_next + (size_t)(j + PF - KSW) * STEP + m * 64);
+                        ring[j % PF][m] = __builtin_nontemporal_load(wp_next + (size_t)(j + PF - KSW) * STEP + m * soff);
                 }
             }
 #pragma unroll
@@ -491,14 +510,15 @@ __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(c
             float s0 = 0.f, s1 = 0.f;
             for (int w = 0; w < p.waves; ++w) {
                 s0 += red[(w * NMAT) * 256 + src];
-                if (NMAT == 2) s1 += red[(w * NMAT + 1) * 256 + src];
+                s1 += red[(w * NMAT + 1) * 256 + src];
             }
-            const int feat = nt * 16 + fi;
             if (MODE == MODE_GU) {
                 const float hval = (s0 / (1.f + expf(-s0))) * s1;
-                p.h[(size_t)a_o * N + feat] = (uint16_t)f32_to_bf16_bits(hval);
+                p.h[(size_t)a_o * N + nt * 16 + fi] = (uint16_t)f32_to_bf16_bits(hval);
             } else {
-                p.ypart[((size_t)s * p.A_tot + a_o) * N + feat] = s0;
+                float* y = p.ypart + ((size_t)s * p.A_tot + a_o) * N + nt * 32 + fi;
+                y[0] = s0;
+                y[16] = s1;
             }
         }
         buf ^= 1;
@@ -628,7 +648,7 @@ struct GemmPlan {
 };
 
 static const int kExactKsw[] = {32, 28, 24, 16, 14, 12, 11, 8, 4};
-static const int kWavePreference[] = {8, 16, 4, 12, 10, 6, 14, 2, 1};
+static const int kWavePreference[] = {16, 8, 4, 12, 10, 6, 14, 2, 1};
 
 static bool is_exact_ksw(int ksw) {
     for (int v : kExactKsw)
@@ -687,7 +707,7 @@ template <int MODE>
 static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, const SpmoeExpertList& list,
                                    const GemmParams& p) {
     const int threads = plan.waves * 64;
-    const size_t lds = (size_t)2 * plan.waves * (MODE == MODE_GU ? 2 : 1) * 256 * sizeof(float) +
+    const size_t lds = (size_t)2 * plan.waves * 2 * 256 * sizeof(float) +
                        (GEMM_MAX_GROUPS + 1) * sizeof(int);
     // cache of grid sizes per (instance, waves): [exact ksw index or generic][waves]
     static int grid_cache[2][16][17];
@@ -763,7 +783,7 @@ hipError_t spmoe_launch_down(hipStream_t stream, int dtype, const SpmoeShape& s,
         p.ks_total = s.f / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
         p.splits = plan.splits;
-        p.n_tiles = s.d / 16;
+        p.n_tiles = s.d / 32;
         p.waves = plan.waves;
         return launch_gemm_bf16<MODE_DOWN>(stream, plan, list, p);
     }

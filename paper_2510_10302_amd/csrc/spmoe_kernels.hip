@@ -69,6 +69,19 @@ __device__ __forceinline__ int wave_min_i(int v) {
                min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
+// Inclusive prefix sum over the 64 lanes: Hillis-Steele inside each row of 16 (row_shr, lanes without a
+// source keep 0), then the last lane of row 0 / row 2 is added to row 1 / row 3 (row_bcast:15) and lane 31
+// to rows 2 and 3 (row_bcast:31).
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __builtin_bit_cast(float, bits16 << 16); }
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs)
@@ -104,29 +117,29 @@ __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n
     }
     for (int s = tid; s < n_shared; s += 256) s_cnt[E + s] = T;
     __syncthreads();
-    // exclusive scan over 512 entries: two per thread, Hillis-Steele on the pair sums
-    const int c0 = s_cnt[2 * tid], c1 = s_cnt[2 * tid + 1];
-    s_scan[tid] = c0 + c1;
-    __syncthreads();
-    for (int off = 1; off < 256; off <<= 1) {
-        int v = (tid >= off) ? s_scan[tid - off] : 0;
-        __syncthreads();
-        s_scan[tid] += v;
-        __syncthreads();
+    // exclusive scan of the counts by wave 0: four consecutive experts per lane, DPP scan of the lane totals
+    if (tid < 64) {
+        int c[4];
+        int tot = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { c[q] = s_cnt[4 * tid + q]; tot += c[q]; }
+        int run = wave_inclusive_scan(tot) - tot;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = 4 * tid + q;
+            if (e < E_tot) { counts[e] = c[q]; offsets[e] = run; }
+            s_scan[e] = run;                  // s_scan now holds the offsets
+            run += c[q];
+        }
+        if (tid == 0) offsets[E_tot] = A + n_shared * T;
     }
-    const int excl = s_scan[tid] - (c0 + c1);
-    __syncthreads();
-    s_cnt[2 * tid] = excl;            // s_cnt now holds the offsets
-    s_cnt[2 * tid + 1] = excl + c0;
-    if (2 * tid < E_tot) { counts[2 * tid] = c0; offsets[2 * tid] = excl; }
-    if (2 * tid + 1 < E_tot) { counts[2 * tid + 1] = c1; offsets[2 * tid + 1] = excl + c0; }
-    if (tid == 0) offsets[E_tot] = A + n_shared * T;
     __syncthreads();
     for (int a = tid; a < A; a += 256) {
         const int e = s_idx[a];
         int rank = 0;
+#pragma unroll 8
         for (int b = 0; b < a; ++b) rank += (s_idx[b] == e);
-        perm[s_cnt[e] + rank] = a;
+        perm[s_scan[e] + rank] = a;
     }
     for (int a = A + tid; a < A + n_shared * T; a += 256) perm[a] = a;
 }
@@ -134,21 +147,71 @@ __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n
 // ---------------------------------------------------------------------------------------------
 // K1: gate logits + softmax + top-k (+ grouping by the last workgroup).  Grid = T, block = 256.
 // ---------------------------------------------------------------------------------------------
-template <typename WT>
-__device__ __forceinline__ void load8_weights(const WT* p, float (&o)[8]);
-template <>
-__device__ __forceinline__ void load8_weights<float>(const float* p, float (&o)[8]) {
-    const float4 a = *reinterpret_cast<const float4*>(p);
-    const float4 b = *reinterpret_cast<const float4*>(p + 4);
-    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
-}
-template <>
-__device__ __forceinline__ void load8_weights<uint16_t>(const uint16_t* p, float (&o)[8]) {
-    const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+// Raw 8-element weight chunk (16 bytes of bf16 or 32 bytes of fp32) and its dot product with 8 x values.
+template <typename WT> struct Chunk8;
+template <> struct Chunk8<uint16_t> {
+    u32x4 v;
+    __device__ __forceinline__ void load(const uint16_t* p) { v = *reinterpret_cast<const u32x4*>(p); }
+    __device__ __forceinline__ float dot(const float4& xa, const float4& xb, float a) const {
+        a = fmaf(xa.x, __builtin_bit_cast(float, v[0] << 16), a); a = fmaf(xa.y, __builtin_bit_cast(float, v[0] & 0xFFFF0000u), a);
+        a = fmaf(xa.z, __builtin_bit_cast(float, v[1] << 16), a); a = fmaf(xa.w, __builtin_bit_cast(float, v[1] & 0xFFFF0000u), a);
+        a = fmaf(xb.x, __builtin_bit_cast(float, v[2] << 16), a); a = fmaf(xb.y, __builtin_bit_cast(float, v[2] & 0xFFFF0000u), a);
+        a = fmaf(xb.z, __builtin_bit_cast(float, v[3] << 16), a); a = fmaf(xb.w, __builtin_bit_cast(float, v[3] & 0xFFFF0000u), a);
+        return a;
+    }
+};
+template <> struct Chunk8<float> {
+    float4 lo, hi;
+    __device__ __forceinline__ void load(const float* p) {
+        lo = *reinterpret_cast<const float4*>(p);
+        hi = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ float dot(const float4& xa, const float4& xb, float a) const {
+        a = fmaf(xa.x, lo.x, a); a = fmaf(xa.y, lo.y, a); a = fmaf(xa.z, lo.z, a); a = fmaf(xa.w, lo.w, a);
+        a = fmaf(xb.x, hi.x, a); a = fmaf(xb.y, hi.y, a); a = fmaf(xb.z, hi.z, a); a = fmaf(xb.w, hi.w, a);
+        return a;
+    }
+};
+
+// logits[e] = sum_j x[j] * Wg[e][j] for the experts of this wave: EPW experts per pass, four waves.
+template <typename WT, int EPW>
+__device__ __forceinline__ void gate_logits_pass(const float* __restrict__ xt, const WT* __restrict__ wg, int E, int d,
+                                                 int wave, int lane, float* s_logit) {
+    constexpr int KI = (sizeof(WT) == 2 ? 16 : 8) / EPW;      // chunks per lane and round
+    for (int e0 = wave * EPW; e0 < E; e0 += 4 * EPW) {
+        float acc[EPW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        o[2 * i] = __builtin_bit_cast(float, v[i] << 16);
-        o[2 * i + 1] = __builtin_bit_cast(float, v[i] & 0xFFFF0000u);
+        for (int q = 0; q < EPW; ++q) acc[q] = 0.f;
+        for (int jb = 0; jb < d; jb += 64 * 8 * KI) {
+            float4 xa[KI], xb[KI];
+            Chunk8<WT> w[KI][EPW];
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const int j = jb + (i * 64 + lane) * 8;
+                if (j < d) {
+                    xa[i] = *reinterpret_cast<const float4*>(xt + j);
+                    xb[i] = *reinterpret_cast<const float4*>(xt + j + 4);
+#pragma unroll
+                    for (int q = 0; q < EPW; ++q)
+                        if (e0 + q < E) w[i][q].load(wg + (size_t)(e0 + q) * d + j);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const int j = jb + (i * 64 + lane) * 8;
+                if (j < d) {
+#pragma unroll
+                    for (int q = 0; q < EPW; ++q)
+                        if (e0 + q < E) acc[q] = w[i][q].dot(xa[i], xb[i], acc[q]);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < EPW; ++q)
+            if (e0 + q < E) {
+                const float sum = wave_sum(acc[q]);
+                if (lane == 0) s_logit[e0 + q] = sum;
+            }
     }
 }
 
@@ -169,37 +232,12 @@ __global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* xt = x + (size_t)t * d;
 
-    // ---- gate logits: each wave scores `epw` experts per pass (their loads are issued together, which
-    //      hides most of the memory latency); lanes split d in chunks of 8 elements
+    // ---- gate logits: each wave scores `epw` experts per pass; all loads of a round (KI chunks of 8
+    //      elements per lane, for every expert of the pass) are issued before the arithmetic starts
     const int epw = (E >= 16) ? 4 : (E >= 8 ? 2 : 1);
-    for (int e0 = wave * epw; e0 < E; e0 += 4 * epw) {
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-        for (int j = lane * 8; j < d; j += 64 * 8) {
-            const float4 xa = *reinterpret_cast<const float4*>(xt + j);
-            const float4 xb = *reinterpret_cast<const float4*>(xt + j + 4);
-            float wv[4][8];
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (q < epw && e0 + q < E) load8_weights<WT>(wg + (size_t)(e0 + q) * d + j, wv[q]);
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (q < epw && e0 + q < E) {
-                    float a = acc[q];
-                    a = fmaf(xa.x, wv[q][0], a); a = fmaf(xa.y, wv[q][1], a);
-                    a = fmaf(xa.z, wv[q][2], a); a = fmaf(xa.w, wv[q][3], a);
-                    a = fmaf(xb.x, wv[q][4], a); a = fmaf(xb.y, wv[q][5], a);
-                    a = fmaf(xb.z, wv[q][6], a); a = fmaf(xb.w, wv[q][7], a);
-                    acc[q] = a;
-                }
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (q < epw && e0 + q < E) {
-                const float sum = wave_sum(acc[q]);
-                if (lane == 0) s_logit[e0 + q] = sum;
-            }
-    }
+    if (epw == 4) gate_logits_pass<WT, 4>(xt, wg, E, d, wave, lane, s_logit);
+    else if (epw == 2) gate_logits_pass<WT, 2>(xt, wg, E, d, wave, lane, s_logit);
+    else gate_logits_pass<WT, 1>(xt, wg, E, d, wave, lane, s_logit);
     __syncthreads();
 
     // ---- wave 0: softmax and k rounds of wave-wide argmax (lane l owns experts l and l + 64)
@@ -648,7 +686,7 @@ struct GemmPlan {
 };
 
 static const int kExactKsw[] = {32, 28, 24, 16, 14, 12, 11, 8, 4};
-static const int kWavePreference[] = {16, 8, 4, 12, 10, 6, 14, 2, 1};
+static const int kWavePreference[] = {16, 8, 11, 12, 10, 14, 4, 6, 2, 1};
 
 static bool is_exact_ksw(int ksw) {
     for (int v : kExactKsw)

@@ -211,3 +211,50 @@ def test_c3_offloaded_stack_teacher_forced(oracle32):
     print("c3 stats", st)
     assert st["prefetch_issued"] > 0 and st["misses"] > 0 and st["hits"] > 0
     L.close()
+
+
+@pytest.mark.parametrize("d,f,E,k,shared,T", [
+    (128, 64, 128, 8, 8, 32),     # every limit of the header at once: 128 experts, top-8, 8 shared, 32 tokens
+    (32, 32, 2, 2, 0, 1),         # the smallest shapes the library accepts
+    (8192, 64, 4, 1, 0, 2),       # widest d_model
+])
+def test_limits_of_the_interface(d, f, E, k, shared, T, oracle32):
+    wl = _wl(d=d, f=f, E=E, k=k, shared=shared, dtype="bf16", layers=1, seed=21, gate_std=0.05, std=0.05)
+    L = _loaded(wl, T)
+    x = si.hidden(21, T, d)
+    rep = check_layer(gpu_layer(L, 0, x), oracle_layer(oracle32, wl, 0, x), k, REL_L2_BF16)
+    print((d, f, E, k, shared, T), rep)
+    L.close()
+
+
+def test_without_renormalisation(oracle32):
+    # renorm_topk = 0: gating scores are the plain softmax probabilities of the selected experts
+    import torch
+    from paper_2510_10302_amd import workload as W
+    wl = _wl(d=256, f=128, E=16, k=4, shared=1, dtype="bf16", layers=1, seed=22, gate_std=0.05, std=0.05)
+    L = W.Loaded(wl, W.make_config(wl, max_tokens=8, renorm=False))
+    x = si.hidden(22, 8, 256)
+    ref = oracle32.moe_layer(x, wl.gate[0], wl.layer_experts(0), 4, shared=wl.shared[0], renorm=False)
+    dx = torch.from_numpy(x).cuda()
+    out = torch.empty((8, 256), device="cuda")
+    idx = torch.empty((8, 4), dtype=torch.int32, device="cuda")
+    w = torch.empty((8, 4), device="cuda")
+    L.ctx.moe_verify_layer(0, dx, out)
+    L.ctx.gate_topk(0, dx, 4, idx, w)
+    L.ctx.sync()
+    assert np.array_equal(idx.cpu().numpy(), ref["idx"])
+    assert np.abs(w.cpu().numpy() - ref["w"]).max() < 2e-5 and np.all(w.cpu().numpy().sum(1) < 0.999)
+    assert rel_l2(out.cpu().numpy(), ref["out"]) < REL_L2_BF16
+    L.close()
+
+
+def test_fp32_weights_mid_size_and_offload(oracle32):
+    # fp32-weight kernels beyond config 1: ragged shapes, shared expert, two token chunks, 2 cache slots
+    from paper_2510_10302_amd import workload as W
+    wl = _wl(d=160, f=96, E=4, k=2, shared=1, dtype="f32", layers=2, seed=23, gate_std=0.05, std=0.05)
+    for slots in (None, 2):
+        L = W.Loaded(wl, W.make_config(wl, max_tokens=20, slots=slots), warm=slots is None)
+        for layer in range(2):
+            x = si.hidden(23, 20, 160, layer=layer)
+            rep = check_layer(gpu_layer(L, layer, x), oracle_layer(oracle32, wl, layer, x), 2, REL_L2_F32)
+        L.close()

@@ -1,6 +1,7 @@
 /* spmoe.h — C ABI of the MI355X-native SP-MoE hot path.
  *
- * One library, one GPU, one caller thread per context.  It implements
+ * One library, one GPU, one caller thread per context (the library runs one worker thread of its own per
+ * context once spmoe_predict_prefetch_async is used).  It implements
  *   (1) the MoE block of the target model on a speculative-verification batch of T tokens
  *       (the N draft tokens plus the last accepted one): gate -> softmax/top-k -> token-to-expert
  *       grouping -> grouped SwiGLU expert FFN -> weighted combination (paper, Eq. 1), and
@@ -20,8 +21,9 @@
  *   - Kernels run on the compute stream passed to spmoe_create() (a hipStream_t, borrowed; NULL is
  *     the default stream).  Hot-path calls are asynchronous with respect to the device, except
  *     where stated (a few integers of routing are needed on the host when experts are offloaded).
- *   - Cache metadata (which expert sits in which slot, LRU order, statistics) changes at call time,
- *     in program order; only the copies themselves are asynchronous.
+ *   - Cache metadata (which expert sits in which slot, LRU order, statistics) changes in the program
+ *     order of the calls (tasks handed to the prefetch worker included); only the copies themselves are
+ *     asynchronous.
  *   - Row-major "canonical" tensors: gate Wg[E][d]; expert W_gate[f][d], W_up[f][d], W_down[d][f];
  *     hidden states x[T][d] fp32; outputs out[T][d] fp32.  d and f must be multiples of 32.
  */
@@ -185,6 +187,19 @@ spmoe_status spmoe_predict_experts(spmoe_ctx* ctx, int layer, const float* dev_d
  * cut to that length.  No-op beyond the cutoff layer.  Returns without waiting for the copies. */
 spmoe_status spmoe_prefetch(spmoe_ctx* ctx, int layer, const int32_t* host_experts, int n);
 
+/* Alg. 1 + Alg. 2 without blocking the caller (the paper's worker-thread "Prefetcher"): the predictor
+ * for n draft states of `layer` is queued on the compute stream, an event is recorded behind it and the
+ * task is pushed to Q_load; a worker thread owned by the context waits for the event, drops cached
+ * experts, chooses LRU victims and issues the copies.  No-op beyond the cutoff layer.  Tasks are
+ * executed in the order they were queued; every other entry point that reads or changes the cache first
+ * waits for the tasks queued before it, so cache contents and statistics are those of the same calls
+ * made synchronously.  Errors met by the worker are returned by the next call on the context.
+ * dev_draft_x must stay valid until the predictor has run (stream order). */
+spmoe_status spmoe_predict_prefetch_async(spmoe_ctx* ctx, int layer, const float* dev_draft_x, int n);
+
+/* Waits until the worker has executed every task queued so far (their copies may still be in flight). */
+spmoe_status spmoe_prefetch_drain(spmoe_ctx* ctx);
+
 /* The MoE block of one layer on T tokens (Eq. 1): out[t] = sum_r w[t][r] * FFN_{idx[t][r]}(x[t])
  * (+ shared experts with weight 1).  Experts already cached are computed first; missing ones are
  * loaded on demand (evicting the LRU head) and computed as their copies land.  When every routed
@@ -192,6 +207,23 @@ spmoe_status spmoe_prefetch(spmoe_ctx* ctx, int layer, const int32_t* host_exper
  * per-expert token counts to reach the host before it returns.  The result does not depend on the
  * cache state. */
 spmoe_status spmoe_moe_verify_layer(spmoe_ctx* ctx, int layer, const float* dev_x, int T, float* dev_out);
+
+/* ---- cutoff-layer policy ("Cutoff layer design") ----------------------------------------------*/
+
+/* Largest cutoff layer L in [0, n_layers) that satisfies the paper's two constraints with k_i
+ * approximated by k (the number of experts predicted per layer):
+ *     N_expert = (L + 1) * k,    m_peak + N_expert * m_expert < m_gpu                     (memory)
+ *     max{ (L - 1) * t_comp + k * t_io,  N_expert * t_io } <= n_layers_draft * t_comp     (overlap)
+ * t_comp: per-layer computation time of the drafting stage, t_io: per-expert loading time (same
+ * unit); memory sizes in the same unit as each other.  *host_cutoff_out = -1 when not even layer 0
+ * can be prefetched under the constraints.  Pure host arithmetic. */
+spmoe_status spmoe_suggest_cutoff(int n_layers, int n_layers_draft, int k, double t_comp, double t_io, double m_peak,
+                                  double m_expert, double m_gpu, int* host_cutoff_out);
+
+/* Profiles the per-expert loading time the policy needs: copies the registered host blob of
+ * (layer, expert) into a temporary HBM buffer `repeats` times on the copy stream and returns the mean
+ * time in ms.  Synchronous; does not touch the cache. */
+spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* ctx, int layer, int expert, int repeats, float* host_ms_out);
 
 /* ---- measurement ------------------------------------------------------------------------------*/
 

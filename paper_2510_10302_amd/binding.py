@@ -22,6 +22,7 @@ DECLARED_SYMBOLS = [
     "spmoe_expert_cache_reset", "spmoe_expert_cache_stats", "spmoe_set_cutoff", "spmoe_gate_topk",
     "spmoe_token_permutation", "spmoe_predict_experts", "spmoe_prefetch", "spmoe_moe_verify_layer",
     "spmoe_profile_begin", "spmoe_profile_collect", "spmoe_last_layer_kernel_ms",
+    "spmoe_suggest_cutoff", "spmoe_measure_expert_load_ms", "spmoe_predict_prefetch_async", "spmoe_prefetch_drain",
 ]
 
 
@@ -98,6 +99,11 @@ def load_library():
         "spmoe_profile_begin": (i32, [vp]),
         "spmoe_profile_collect": (i32, [vp, vp, i32, vp]),
         "spmoe_last_layer_kernel_ms": (i32, [vp, vp]),
+        "spmoe_suggest_cutoff": (i32, [i32, i32, i32, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+                                       ctypes.c_double, ctypes.c_double, vp]),
+        "spmoe_measure_expert_load_ms": (i32, [vp, i32, i32, i32, vp]),
+        "spmoe_predict_prefetch_async": (i32, [vp, i32, vp, i32]),
+        "spmoe_prefetch_drain": (i32, [vp]),
     }
     assert sorted(sig) == sorted(DECLARED_SYMBOLS)
     for name, (res, args) in sig.items():
@@ -132,6 +138,16 @@ def pack_expert(cfg, w_gate, w_up, w_down, out=None):
     if st != 0:
         raise SpmoeError(st, "spmoe_pack_expert")
     return out
+
+
+def suggest_cutoff(n_layers, n_layers_draft, k, t_comp, t_io, m_peak, m_expert, m_gpu):
+    """Largest cutoff layer allowed by the paper's memory and overlap constraints (-1: none)."""
+    out = ctypes.c_int32(-2)
+    st = load_library().spmoe_suggest_cutoff(n_layers, n_layers_draft, k, t_comp, t_io, m_peak, m_expert, m_gpu,
+                                             ctypes.addressof(out))
+    if st != 0:
+        raise SpmoeError(st, "spmoe_suggest_cutoff")
+    return out.value
 
 
 def _host_ptr(buf):
@@ -255,6 +271,13 @@ class Context:
         arr = np.ascontiguousarray(experts, dtype=np.int32)
         self._check(self.lib.spmoe_prefetch(self.h, layer, arr.ctypes.data, arr.size), "spmoe_prefetch")
 
+    def predict_prefetch_async(self, layer, dev_draft_x):
+        self._check(self.lib.spmoe_predict_prefetch_async(self.h, layer, _dev_ptr(dev_draft_x, self._torch.float32),
+                                                          dev_draft_x.shape[0]), "spmoe_predict_prefetch_async")
+
+    def prefetch_drain(self):
+        self._check(self.lib.spmoe_prefetch_drain(self.h), "spmoe_prefetch_drain")
+
     def moe_verify_layer(self, layer, dev_x, dev_out):
         t = self._torch
         self._check(self.lib.spmoe_moe_verify_layer(self.h, layer, _dev_ptr(dev_x, t.float32), dev_x.shape[0],
@@ -271,6 +294,12 @@ class Context:
                     "spmoe_profile_collect")
         return [dict(kind=r.kind, layer=r.layer, expert=r.expert, t0=r.t_begin_ms, t1=r.t_end_ms)
                 for r in recs[: min(n.value, cap)]]
+
+    def measure_expert_load_ms(self, layer, expert, repeats=3):
+        ms = ctypes.c_float(0)
+        self._check(self.lib.spmoe_measure_expert_load_ms(self.h, layer, expert, repeats, ctypes.addressof(ms)),
+                    "spmoe_measure_expert_load_ms")
+        return ms.value
 
     def last_layer_kernel_ms(self):
         ms = (ctypes.c_float * 4)()

@@ -4,11 +4,14 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <condition_variable>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "spmoe_internal.h"
@@ -40,6 +43,18 @@ struct TimedSpan {
     int kind, layer, expert;
 };
 
+// One entry of Q_load (Alg. 1 l.9-10): a prediction whose routing is still on its way to the host,
+// with the event the prefetch worker waits on (Alg. 2 l.5) before it turns it into copies.
+struct LoadTask {
+    int layer = 0, n = 0;
+    int32_t* dev_idx = nullptr;   // [Tmax * pred_k]
+    float* dev_p = nullptr;
+    int32_t* host_idx = nullptr;  // pinned
+    float* host_p = nullptr;
+    hipEvent_t ev = nullptr;
+};
+constexpr int kLoadQueueSlots = 128;
+
 }  // namespace
 
 struct spmoe_ctx {
@@ -65,6 +80,17 @@ struct spmoe_ctx {
     int32_t* host_pred_idx = nullptr; // [Tmax * pred_k]
     float* host_pred_p = nullptr;     // [Tmax * pred_k]
     hipEvent_t host_ready = nullptr;
+
+    // prefetch worker ("Prefetcher" thread of Alg. 2) and its task queue Q_load
+    std::mutex meta_mu;               // guards cache metadata, statistics, the copy stream's issue order
+    std::mutex q_mu;                  // guards the queue counters below
+    std::condition_variable q_work, q_done;
+    std::vector<LoadTask> q_load;     // ring of kLoadQueueSlots entries, allocated at the first asynchronous call
+    uint64_t q_enqueued = 0, q_started = 0, q_finished = 0;
+    bool q_stop = false;
+    std::thread worker;
+    spmoe_status worker_status = SPMOE_OK;
+    int device = 0;
 
     // profiling
     bool profiling = false;
@@ -244,6 +270,162 @@ spmoe_status check_layer(spmoe_ctx* c, int layer) {
     return SPMOE_OK;
 }
 
+// Host half of Alg. 1 (lines 3-6) on routing that has reached the host: rank the predicted experts
+// (most-voted first, then larger summed probability, then lower index), drop the ones already in
+// Q_cache and move those to the queue tail.  Returns the number of experts left in out_ids.
+spmoe_status rank_and_filter(spmoe_ctx* c, Layer& L, const int32_t* idx, const float* prob, int n, int32_t* out_ids,
+                             int* n_out) {
+    const int pk = c->cfg.pred_k, E = c->cfg.n_experts;
+    int votes[SPMOE_MAX_EXPERTS] = {0};
+    double psum[SPMOE_MAX_EXPERTS] = {0.0};
+    for (int i = 0; i < n * pk; ++i) {
+        const int e = idx[i];
+        if (e < 0 || e >= E) return fail(c, SPMOE_EHIP, "prediction kernel returned expert %d", e);
+        votes[e] += 1;
+        psum[e] += prob[i];
+    }
+    std::vector<int> order;
+    for (int e = 0; e < E; ++e)
+        if (votes[e] > 0) order.push_back(e);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
+        if (votes[a] != votes[b]) return votes[a] > votes[b];
+        if (psum[a] != psum[b]) return psum[a] > psum[b];
+        return a < b;
+    });
+    int m = 0;
+    for (int e : order) {
+        if (L.slot_of[e] < 0) out_ids[m++] = e;   // Alg. 1: predicted experts that are already cached are dropped ...
+        else lru_touch(L, e);                     // ... and moved to the tail, so this task cannot evict them
+    }
+    *n_out = m;
+    return SPMOE_OK;
+}
+
+// Alg. 2 for one task (arguments already validated; metadata lock held).
+spmoe_status prefetch_locked(spmoe_ctx* c, int layer, const int32_t* experts, int n) {
+    Layer& L = c->layers[layer];
+    if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer) return SPMOE_OK;   // Alg. 1: only l <= L
+    std::vector<int> uniq;
+    for (int i = 0; i < n; ++i)
+        if (std::find(uniq.begin(), uniq.end(), experts[i]) == uniq.end()) uniq.push_back(experts[i]);
+    if ((int)uniq.size() > c->cfg.cache_slots_per_layer) uniq.resize(c->cfg.cache_slots_per_layer);
+    for (int e : uniq)
+        if (L.slot_of[e] >= 0) lru_touch(L, e);        // predicted and cached: moved to the tail, not loaded
+    for (int e : uniq) {                               // Alg. 2: as many victims as loads, copies back to back
+        if (L.slot_of[e] >= 0) continue;
+        if (!L.host_blob[e]) return fail(c, SPMOE_ESTATE, "expert %d of layer %d is not registered", e, layer);
+        const int s = take_slot(c, L);
+        spmoe_status st = issue_copy(c, layer, e, s, true);
+        if (st != SPMOE_OK) return st;
+    }
+    return SPMOE_OK;
+}
+
+// Launches the predictor (target gate of `layer` on n draft states, top pred_k, plain softmax
+// probabilities) and the two small device-to-host copies of its result, all on the compute stream.
+spmoe_status launch_prediction(spmoe_ctx* c, int layer, const float* dev_draft_x, int n, int32_t* dev_idx, float* dev_p,
+                               int32_t* host_idx, float* host_p) {
+    const int pk = c->cfg.pred_k;
+    size_t span;
+    spmoe_status st = span_begin(c, c->compute, 3, layer, n, &span);
+    if (st != SPMOE_OK) return st;
+    HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_draft_x, c->layers[layer].gate, n,
+                                      c->cfg.n_experts, c->cfg.d_model, pk, 0, dev_idx, dev_p, nullptr, 0, nullptr, nullptr,
+                                      nullptr, nullptr));
+    HIP_TRY(c, hipMemcpyAsync(host_idx, dev_idx, sizeof(int32_t) * n * pk, hipMemcpyDeviceToHost, c->compute));
+    HIP_TRY(c, hipMemcpyAsync(host_p, dev_p, sizeof(float) * n * pk, hipMemcpyDeviceToHost, c->compute));
+    return span_end(c, c->compute, span);
+}
+
+spmoe_status sync_streams(spmoe_ctx* c) {
+    HIP_TRY(c, hipStreamSynchronize(c->copy));
+    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    return SPMOE_OK;
+}
+
+// Waits until the prefetch worker has executed every task queued so far; returns (and clears) its error.
+spmoe_status drain(spmoe_ctx* c) {
+    std::unique_lock<std::mutex> lk(c->q_mu);
+    c->q_done.wait(lk, [&] { return c->q_finished == c->q_enqueued; });
+    const spmoe_status st = c->worker_status;
+    c->worker_status = SPMOE_OK;
+    return st;
+}
+
+// Entry points that read or change cache metadata first let the worker finish what was queued before
+// them (so the metadata sequence is the program order of the calls) and then hold the metadata lock.
+struct Guard {
+    std::unique_lock<std::mutex> lk;
+    spmoe_status st;
+    explicit Guard(spmoe_ctx* c) : st(drain(c)) { lk = std::unique_lock<std::mutex>(c->meta_mu); }
+};
+
+// The "Prefetcher" thread of Alg. 2: pops tasks in order, waits for the task's event, then issues the copies.
+void worker_main(spmoe_ctx* c) {
+    (void)hipSetDevice(c->device);
+    for (;;) {
+        LoadTask* t = nullptr;
+        {
+            std::unique_lock<std::mutex> lk(c->q_mu);
+            c->q_work.wait(lk, [&] { return c->q_stop || c->q_started < c->q_enqueued; });
+            if (c->q_started == c->q_enqueued) return;       // stopping and nothing left
+            t = &c->q_load[c->q_started % kLoadQueueSlots];
+            c->q_started += 1;
+        }
+        spmoe_status st = SPMOE_OK;
+        if (hipEventSynchronize(t->ev) != hipSuccess) {      // Alg. 2: Event.wait()
+            (void)hipGetLastError();
+            st = SPMOE_EHIP;
+        } else {
+            std::lock_guard<std::mutex> meta(c->meta_mu);
+            int32_t ids[SPMOE_MAX_EXPERTS];
+            int m = 0;
+            st = rank_and_filter(c, c->layers[t->layer], t->host_idx, t->host_p, t->n, ids, &m);
+            if (st == SPMOE_OK) st = prefetch_locked(c, t->layer, ids, m);
+        }
+        {
+            std::lock_guard<std::mutex> lk(c->q_mu);
+            if (st != SPMOE_OK && c->worker_status == SPMOE_OK) c->worker_status = st;
+            c->q_finished += 1;
+        }
+        c->q_done.notify_all();
+    }
+}
+
+spmoe_status start_worker(spmoe_ctx* c) {
+    if (c->worker.joinable()) return SPMOE_OK;
+    const int pk = std::max(c->cfg.pred_k, 1), Tm = c->cfg.max_tokens;
+    c->q_load.resize(kLoadQueueSlots);
+    for (auto& t : c->q_load) {
+        HIP_TRY(c, hipMalloc(&t.dev_idx, sizeof(int32_t) * Tm * pk));
+        HIP_TRY(c, hipMalloc(&t.dev_p, sizeof(float) * Tm * pk));
+        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&t.host_idx), sizeof(int32_t) * Tm * pk, hipHostMallocDefault));
+        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&t.host_p), sizeof(float) * Tm * pk, hipHostMallocDefault));
+        HIP_TRY(c, hipEventCreateWithFlags(&t.ev, hipEventDisableTiming));
+    }
+    c->worker = std::thread(worker_main, c);
+    return SPMOE_OK;
+}
+
+void stop_worker(spmoe_ctx* c) {
+    if (c->worker.joinable()) {
+        {
+            std::lock_guard<std::mutex> lk(c->q_mu);
+            c->q_stop = true;
+        }
+        c->q_work.notify_all();
+        c->worker.join();
+    }
+    for (auto& t : c->q_load) {
+        if (t.dev_idx) (void)hipFree(t.dev_idx);
+        if (t.dev_p) (void)hipFree(t.dev_p);
+        if (t.host_idx) (void)hipHostFree(t.host_idx);
+        if (t.host_p) (void)hipHostFree(t.host_p);
+        if (t.ev) (void)hipEventDestroy(t.ev);
+    }
+    c->q_load.clear();
+}
+
 }  // namespace
 
 extern "C" {
@@ -312,6 +494,7 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
     if (!c) return SPMOE_ENOMEM;
     c->cfg = *cfg;
     c->compute = static_cast<hipStream_t>(compute_stream);
+    (void)hipGetDevice(&c->device);
     c->blob_bytes = spmoe_expert_blob_bytes(cfg);
     memset(&c->stats, 0, sizeof c->stats);
     const int E = cfg->n_experts, S = cfg->cache_slots_per_layer, Tm = cfg->max_tokens;
@@ -376,6 +559,7 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
 
 spmoe_status spmoe_destroy(spmoe_ctx* c) {
     if (!c) return SPMOE_OK;
+    stop_worker(c);
     (void)hipStreamSynchronize(c->compute);
     if (c->copy) (void)hipStreamSynchronize(c->copy);
     free_spans(c);
@@ -409,9 +593,9 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
 
 spmoe_status spmoe_sync(spmoe_ctx* c) {
     if (!c) return SPMOE_EINVAL;
-    HIP_TRY(c, hipStreamSynchronize(c->copy));
-    HIP_TRY(c, hipStreamSynchronize(c->compute));
-    return SPMOE_OK;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
+    return sync_streams(c);
 }
 
 const char* spmoe_last_error(const spmoe_ctx* c) { return c ? c->err.c_str() : ""; }
@@ -419,6 +603,8 @@ const char* spmoe_last_error(const spmoe_ctx* c) { return c ? c->err.c_str() : "
 spmoe_status spmoe_set_gate(spmoe_ctx* c, int layer, const void* dev_wg) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (!dev_wg) return fail(c, SPMOE_EINVAL, "gate pointer is NULL");
     c->layers[layer].gate = dev_wg;
     return SPMOE_OK;
@@ -426,6 +612,8 @@ spmoe_status spmoe_set_gate(spmoe_ctx* c, int layer, const void* dev_wg) {
 
 spmoe_status spmoe_set_cutoff(spmoe_ctx* c, int cutoff_layer) {
     if (!c) return SPMOE_EINVAL;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     c->cfg.cutoff_layer = cutoff_layer;
     return SPMOE_OK;
 }
@@ -433,6 +621,8 @@ spmoe_status spmoe_set_cutoff(spmoe_ctx* c, int cutoff_layer) {
 spmoe_status spmoe_expert_cache_register(spmoe_ctx* c, int layer, int expert, const void* pinned_blob) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (expert < 0 || expert >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", expert);
     if (!pinned_blob) return fail(c, SPMOE_EINVAL, "blob pointer is NULL");
     c->layers[layer].host_blob[expert] = pinned_blob;
@@ -442,6 +632,8 @@ spmoe_status spmoe_expert_cache_register(spmoe_ctx* c, int layer, int expert, co
 spmoe_status spmoe_expert_cache_register_shared(spmoe_ctx* c, int layer, int idx, const void* pinned_blob) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (idx < 0 || idx >= c->cfg.n_shared) return fail(c, SPMOE_ERANGE, "shared expert %d out of range", idx);
     if (!pinned_blob) return fail(c, SPMOE_EINVAL, "blob pointer is NULL");
     HIP_TRY(c, hipStreamSynchronize(c->compute));
@@ -452,6 +644,8 @@ spmoe_status spmoe_expert_cache_register_shared(spmoe_ctx* c, int layer, int idx
 spmoe_status spmoe_expert_cache_warm(spmoe_ctx* c, int layer, const int32_t* host_experts, int n) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (n < 0 || (n > 0 && !host_experts)) return fail(c, SPMOE_EINVAL, "bad expert list");
     Layer& L = c->layers[layer];
     for (int i = 0; i < n; ++i) {
@@ -478,6 +672,8 @@ spmoe_status spmoe_expert_cache_warm(spmoe_ctx* c, int layer, const int32_t* hos
 spmoe_status spmoe_expert_cache_lookup(spmoe_ctx* c, int layer, int expert, int32_t* host_slot_out) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (expert < 0 || expert >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", expert);
     if (!host_slot_out) return fail(c, SPMOE_EINVAL, "output pointer is NULL");
     *host_slot_out = c->layers[layer].slot_of[expert];
@@ -487,6 +683,8 @@ spmoe_status spmoe_expert_cache_lookup(spmoe_ctx* c, int layer, int expert, int3
 spmoe_status spmoe_expert_cache_contents(spmoe_ctx* c, int layer, int32_t* host_lru_order_out, int32_t* host_n_out) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (!host_lru_order_out || !host_n_out) return fail(c, SPMOE_EINVAL, "output pointer is NULL");
     const Layer& L = c->layers[layer];
     for (size_t i = 0; i < L.lru.size(); ++i) host_lru_order_out[i] = L.lru[i];
@@ -496,7 +694,9 @@ spmoe_status spmoe_expert_cache_contents(spmoe_ctx* c, int layer, int32_t* host_
 
 spmoe_status spmoe_expert_cache_reset(spmoe_ctx* c) {
     if (!c) return SPMOE_EINVAL;
-    spmoe_status st = spmoe_sync(c);
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
+    spmoe_status st = sync_streams(c);
     if (st != SPMOE_OK) return st;
     for (auto& L : c->layers) {
         L.lru.clear();
@@ -514,6 +714,8 @@ spmoe_status spmoe_expert_cache_reset(spmoe_ctx* c) {
 
 spmoe_status spmoe_expert_cache_stats(spmoe_ctx* c, spmoe_stats* host_out) {
     if (!c) return SPMOE_EINVAL;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (!host_out) return fail(c, SPMOE_EINVAL, "output pointer is NULL");
     *host_out = c->stats;
     return SPMOE_OK;
@@ -525,6 +727,8 @@ spmoe_status spmoe_gate_topk(spmoe_ctx* c, int layer, const float* dev_x, int T,
                              float* dev_logits) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (T < 0 || T > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "T=%d exceeds max_tokens=%d", T, c->cfg.max_tokens);
     if (k < 1 || k > SPMOE_MAX_TOPK || k > c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "k=%d out of range", k);
     if (T == 0) return SPMOE_OK;   // an empty batch is a no-op (its pointers may be NULL)
@@ -539,6 +743,8 @@ spmoe_status spmoe_gate_topk(spmoe_ctx* c, int layer, const float* dev_x, int T,
 spmoe_status spmoe_token_permutation(spmoe_ctx* c, const int32_t* dev_idx, int T, int k, int32_t* dev_counts,
                                      int32_t* dev_offsets, int32_t* dev_perm) {
     if (!c) return SPMOE_EINVAL;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (!dev_idx || !dev_counts || !dev_offsets || !dev_perm) return fail(c, SPMOE_EINVAL, "NULL device pointer");
     if (T < 0 || T > SPMOE_MAX_TOKENS) return fail(c, SPMOE_ERANGE, "T=%d out of range", T);
     if (k < 1 || k > SPMOE_MAX_TOPK) return fail(c, SPMOE_ERANGE, "k=%d out of range", k);
@@ -550,6 +756,8 @@ spmoe_status spmoe_predict_experts(spmoe_ctx* c, int layer, const float* dev_dra
                                    int32_t* host_n_out) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (!dev_draft_x || !host_ids_out || !host_n_out) return fail(c, SPMOE_EINVAL, "NULL pointer");
     if (n < 0 || n > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "n=%d exceeds max_tokens=%d", n, c->cfg.max_tokens);
     if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer || n == 0 || c->cfg.pred_k < 1) {   // Alg. 1: only l <= L
@@ -558,48 +766,64 @@ spmoe_status spmoe_predict_experts(spmoe_ctx* c, int layer, const float* dev_dra
     }
     Layer& L = c->layers[layer];
     if (!L.gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
-    const int pk = c->cfg.pred_k, E = c->cfg.n_experts;
-    size_t span;
-    st = span_begin(c, c->compute, 3, layer, n, &span);
-    if (st != SPMOE_OK) return st;
-    // plain softmax probabilities (no renormalisation) rank experts predicted by several draft tokens
-    HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_draft_x, L.gate, n, E, c->cfg.d_model, pk, 0,
-                                      c->pred.idx, c->pred.w, nullptr, 0, nullptr, nullptr, nullptr, nullptr));
-    HIP_TRY(c, hipMemcpyAsync(c->host_pred_idx, c->pred.idx, sizeof(int32_t) * n * pk, hipMemcpyDeviceToHost, c->compute));
-    HIP_TRY(c, hipMemcpyAsync(c->host_pred_p, c->pred.w, sizeof(float) * n * pk, hipMemcpyDeviceToHost, c->compute));
-    st = span_end(c, c->compute, span);
+    st = launch_prediction(c, layer, dev_draft_x, n, c->pred.idx, c->pred.w, c->host_pred_idx, c->host_pred_p);
     if (st != SPMOE_OK) return st;
     HIP_TRY(c, hipEventRecord(c->host_ready, c->compute));
     HIP_TRY(c, hipEventSynchronize(c->host_ready));
-
-    int votes[SPMOE_MAX_EXPERTS] = {0};
-    double psum[SPMOE_MAX_EXPERTS] = {0.0};
-    for (int i = 0; i < n * pk; ++i) {
-        const int e = c->host_pred_idx[i];
-        if (e < 0 || e >= E) return fail(c, SPMOE_EHIP, "prediction kernel returned expert %d", e);
-        votes[e] += 1;
-        psum[e] += c->host_pred_p[i];
-    }
-    std::vector<int> order;
-    for (int e = 0; e < E; ++e)
-        if (votes[e] > 0) order.push_back(e);
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) {
-        if (votes[a] != votes[b]) return votes[a] > votes[b];
-        if (psum[a] != psum[b]) return psum[a] > psum[b];
-        return a < b;
-    });
     int m = 0;
-    for (int e : order) {
-        if (L.slot_of[e] < 0) host_ids_out[m++] = e;   // Alg. 1: predicted experts that are already cached are dropped ...
-        else lru_touch(L, e);                          // ... and moved to the tail, so this task cannot evict them
-    }
+    st = rank_and_filter(c, L, c->host_pred_idx, c->host_pred_p, n, host_ids_out, &m);
+    if (st != SPMOE_OK) return st;
     *host_n_out = m;
     return SPMOE_OK;
+}
+
+spmoe_status spmoe_predict_prefetch_async(spmoe_ctx* c, int layer, const float* dev_draft_x, int n) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    if (n < 0 || n > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "n=%d exceeds max_tokens=%d", n, c->cfg.max_tokens);
+    if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer || n == 0 || c->cfg.pred_k < 1) return SPMOE_OK;
+    if (!dev_draft_x) return fail(c, SPMOE_EINVAL, "NULL pointer");
+    if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
+    LoadTask* t = nullptr;
+    {
+        std::unique_lock<std::mutex> lk(c->q_mu);
+        if (c->worker_status != SPMOE_OK) {
+            st = c->worker_status;
+            c->worker_status = SPMOE_OK;
+            return st;
+        }
+        // a free ring entry: the worker must have finished the task that used it last
+        c->q_done.wait(lk, [&] { return c->q_enqueued - c->q_finished < (uint64_t)kLoadQueueSlots; });
+    }
+    {
+        std::lock_guard<std::mutex> meta(c->meta_mu);      // profiling spans and the error string are shared
+        st = start_worker(c);
+        if (st != SPMOE_OK) return st;
+        t = &c->q_load[c->q_enqueued % kLoadQueueSlots];   // only this thread advances q_enqueued
+        t->layer = layer;
+        t->n = n;
+        st = launch_prediction(c, layer, dev_draft_x, n, t->dev_idx, t->dev_p, t->host_idx, t->host_p);
+        if (st != SPMOE_OK) return st;
+        HIP_TRY(c, hipEventRecord(t->ev, c->compute));     // Alg. 1: Event.record, then Q_load.push_back
+    }
+    {
+        std::lock_guard<std::mutex> lk(c->q_mu);
+        c->q_enqueued += 1;
+    }
+    c->q_work.notify_one();
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_prefetch_drain(spmoe_ctx* c) {
+    if (!c) return SPMOE_EINVAL;
+    return drain(c);
 }
 
 spmoe_status spmoe_prefetch(spmoe_ctx* c, int layer, const int32_t* host_experts, int n) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (n < 0 || (n > 0 && !host_experts)) return fail(c, SPMOE_EINVAL, "bad expert list");
     Layer& L = c->layers[layer];
     for (int i = 0; i < n; ++i) {
@@ -607,25 +831,14 @@ spmoe_status spmoe_prefetch(spmoe_ctx* c, int layer, const int32_t* host_experts
         if (e < 0 || e >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", e);
         if (!L.host_blob[e]) return fail(c, SPMOE_ESTATE, "expert %d of layer %d is not registered", e, layer);
     }
-    if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer) return SPMOE_OK;   // Alg. 1: only l <= L
-    std::vector<int> uniq;
-    for (int i = 0; i < n; ++i)
-        if (std::find(uniq.begin(), uniq.end(), host_experts[i]) == uniq.end()) uniq.push_back(host_experts[i]);
-    if ((int)uniq.size() > c->cfg.cache_slots_per_layer) uniq.resize(c->cfg.cache_slots_per_layer);
-    for (int e : uniq)
-        if (L.slot_of[e] >= 0) lru_touch(L, e);        // predicted and cached: moved to the tail, not loaded
-    for (int e : uniq) {                               // Alg. 2: as many victims as loads, copies back to back
-        if (L.slot_of[e] >= 0) continue;
-        const int s = take_slot(c, L);
-        st = issue_copy(c, layer, e, s, true);
-        if (st != SPMOE_OK) return st;
-    }
-    return SPMOE_OK;
+    return prefetch_locked(c, layer, host_experts, n);
 }
 
 spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x, int T, float* dev_out) {
     spmoe_status st = check_layer(c, layer);
     if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (T < 0 || T > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "T=%d exceeds max_tokens=%d", T, c->cfg.max_tokens);
     if (T == 0) return SPMOE_OK;   // an empty batch is a no-op (its pointers may be NULL)
     if (!dev_x || !dev_out) return fail(c, SPMOE_EINVAL, "NULL device pointer");
@@ -730,10 +943,61 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
     return span_end(c, c->compute, span);
 }
 
+// ---- cutoff-layer policy ----------------------------------------------------------------------------
+
+spmoe_status spmoe_suggest_cutoff(int n_layers, int n_layers_draft, int k, double t_comp, double t_io, double m_peak,
+                                  double m_expert, double m_gpu, int* host_cutoff_out) {
+    if (!host_cutoff_out || n_layers < 1 || n_layers_draft < 1 || k < 1) return SPMOE_EINVAL;
+    if (!(t_comp > 0) || !(t_io > 0) || m_expert < 0 || m_peak < 0) return SPMOE_EINVAL;
+    int best = -1;
+    for (int L = 0; L < n_layers; ++L) {
+        const double n_expert = (double)(L + 1) * k;
+        const bool mem_ok = m_peak + n_expert * m_expert < m_gpu;
+        const double finish = std::max((L - 1) * t_comp + k * t_io, n_expert * t_io);
+        const bool time_ok = finish <= n_layers_draft * t_comp;
+        if (mem_ok && time_ok) best = L;
+    }
+    *host_cutoff_out = best;
+    return SPMOE_OK;
+}
+
+spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* c, int layer, int expert, int repeats, float* host_ms_out) {
+    spmoe_status st = check_layer(c, layer);
+    if (st != SPMOE_OK) return st;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
+    if (expert < 0 || expert >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", expert);
+    if (!host_ms_out || repeats < 1) return fail(c, SPMOE_EINVAL, "bad arguments");
+    const void* src = c->layers[layer].host_blob[expert];
+    if (!src) return fail(c, SPMOE_ESTATE, "expert %d of layer %d is not registered", expert, layer);
+    void* tmp = nullptr;
+    if (hipMalloc(&tmp, c->blob_bytes) != hipSuccess) { (void)hipGetLastError(); return fail(c, SPMOE_ENOMEM, "hipMalloc"); }
+    hipEvent_t a = nullptr, b = nullptr;
+    spmoe_status res = SPMOE_OK;
+    float ms = 0.f;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) res = SPMOE_EHIP;
+    if (res == SPMOE_OK) {
+        bool ok = hipMemcpyAsync(tmp, src, c->blob_bytes, hipMemcpyHostToDevice, c->copy) == hipSuccess;   // warm-up
+        ok = ok && hipEventRecord(a, c->copy) == hipSuccess;
+        for (int i = 0; ok && i < repeats; ++i)
+            ok = hipMemcpyAsync(tmp, src, c->blob_bytes, hipMemcpyHostToDevice, c->copy) == hipSuccess;
+        ok = ok && hipEventRecord(b, c->copy) == hipSuccess && hipEventSynchronize(b) == hipSuccess &&
+             hipEventElapsedTime(&ms, a, b) == hipSuccess;
+        if (!ok) res = fail(c, SPMOE_EHIP, "timed copy failed: %s", hipGetErrorString(hipGetLastError()));
+    }
+    if (a) (void)hipEventDestroy(a);
+    if (b) (void)hipEventDestroy(b);
+    (void)hipFree(tmp);
+    if (res == SPMOE_OK) *host_ms_out = ms / repeats;
+    return res;
+}
+
 // ---- measurement ------------------------------------------------------------------------------------
 
 spmoe_status spmoe_profile_begin(spmoe_ctx* c) {
     if (!c) return SPMOE_EINVAL;
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     free_spans(c);
     if (!c->prof_origin) HIP_TRY(c, hipEventCreate(&c->prof_origin));
     HIP_TRY(c, hipStreamSynchronize(c->copy));
@@ -747,8 +1011,10 @@ spmoe_status spmoe_profile_begin(spmoe_ctx* c) {
 spmoe_status spmoe_profile_collect(spmoe_ctx* c, spmoe_profile_record* host_out, int cap, int* host_n_out) {
     if (!c) return SPMOE_EINVAL;
     if (!host_n_out || (cap > 0 && !host_out)) return fail(c, SPMOE_EINVAL, "NULL output pointer");
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     c->profiling = false;
-    spmoe_status st = spmoe_sync(c);
+    spmoe_status st = sync_streams(c);
     if (st != SPMOE_OK) return st;
     const int n = (int)c->spans.size();
     for (int i = 0; i < n && i < cap; ++i) {
@@ -765,6 +1031,8 @@ spmoe_status spmoe_profile_collect(spmoe_ctx* c, spmoe_profile_record* host_out,
 spmoe_status spmoe_last_layer_kernel_ms(spmoe_ctx* c, float host_ms_out[4]) {
     if (!c) return SPMOE_EINVAL;
     if (!host_ms_out) return fail(c, SPMOE_EINVAL, "NULL output pointer");
+    Guard guard(c);
+    if (guard.st != SPMOE_OK) return guard.st;
     if (!c->kev[0]) return fail(c, SPMOE_ESTATE, "no verify-layer call has run with profiling on");
     HIP_TRY(c, hipStreamSynchronize(c->compute));
     float ms[4] = {0.f, 0.f, 0.f, 0.f};

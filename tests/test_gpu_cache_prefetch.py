@@ -115,3 +115,51 @@ def test_profile_records_cover_copies_and_layers():
     assert all(r["t1"] >= r["t0"] >= 0 for r in recs)
     assert len(ms) == 4 and all(m >= 0 for m in ms) and ms[1] > 0 and ms[2] > 0
     L.close()
+
+
+def test_async_worker_matches_synchronous_calls(oracle32):
+    # The worker-thread path (predict + prefetch queued without blocking) must leave the cache, the
+    # statistics and the outputs exactly as the same calls made synchronously do.
+    import torch
+    T, n_layers = 8, 3
+    results = []
+    for mode in ("sync", "async"):
+        wl, L = _setup(slots=3, cutoff=1, layers=n_layers)
+        outs, contents = [], []
+        for it in range(5):
+            xs = [si.hidden(12, T, 256, iteration=it, layer=l) for l in range(n_layers)]
+            drafts = [torch.from_numpy(xs[l] + si.draft_noise(12, T, 256, 0.3, iteration=it, layer=l)).cuda()
+                      for l in range(n_layers)]
+            for j in range(T - 1):                     # one task per draft token and layer, as in the drafting stage
+                for l in range(n_layers):
+                    if mode == "sync":
+                        L.ctx.prefetch(l, L.ctx.predict_experts(l, drafts[l][j:j + 1]))
+                    else:
+                        L.ctx.predict_prefetch_async(l, drafts[l][j:j + 1])
+            for l in range(n_layers):
+                outs.append(gpu_layer(L, l, xs[l])["out"])
+                contents.append(L.ctx.expert_cache_contents(l))
+        L.ctx.prefetch_drain()
+        results.append((outs, contents, L.ctx.expert_cache_stats()))
+        L.close()
+    (o1, c1, s1), (o2, c2, s2) = results
+    assert c1 == c2
+    for key in s1:
+        if key != "late_hits":                         # timing-dependent: how many copies were still in flight
+            assert s1[key] == s2[key], key
+    assert all(np.array_equal(a, b) for a, b in zip(o1, o2))
+    assert s2["prefetch_issued"] > 0
+
+
+def test_measured_load_time_and_suggested_cutoff():
+    import paper_2510_10302_amd as sp
+    wl, L = _setup(slots=2, cutoff=0, layers=2, d=1024, f=2048)
+    ms = L.ctx.measure_expert_load_ms(0, 1, repeats=3)
+    nbytes = 3 * 1024 * 2048 * 2
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    print("expert load %.3f ms -> %.1f GB/s" % (ms, gbs))
+    assert 1.0 < gbs < 200.0
+    # with a per-layer compute time of 4 loads, the overlap constraint (L+1)*k*t_io <= L_all*t_comp gives L = 7 of 2 layers -> capped
+    assert sp.suggest_cutoff(2, 2, 1, 4 * ms, ms, 0.0, nbytes, 1e12) == 1
+    assert sp.suggest_cutoff(2, 2, 1, 0.25 * ms, ms, 0.0, nbytes, 1e12) == -1
+    L.close()

@@ -77,3 +77,23 @@ def test_argument_validation_without_a_gpu(sp):
     assert lib.spmoe_sync(None) == 1
     with pytest.raises(ValueError):
         sp.pack_expert(cfg, np.zeros((64, 64), np.float32), np.zeros((64, 64), np.float32), np.zeros((64, 64), np.float32))
+
+
+def test_cutoff_policy_hand_worked(sp):
+    # "Cutoff layer design": N = (L+1)k; m_peak + N*m_exp < m_gpu; max{(L-1)t_c + k*t_io, N*t_io} <= L_all*t_c.
+    # Hand-worked: L_all = 32, t_c = 1, t_io = 2, k = 1, no memory pressure: N*t_io = 2(L+1) <= 32 -> L = 15.
+    assert sp.suggest_cutoff(32, 32, 1, 1.0, 2.0, 0.0, 1.0, 1e9) == 15
+    # memory binds first: 10 + (L+1)*1 < 20 -> L + 1 <= 9 -> L = 8
+    assert sp.suggest_cutoff(32, 32, 1, 1.0, 2.0, 10.0, 1.0, 20.0) == 8
+    # k = 2: 2(L+1)*2 <= 32 -> L = 7
+    assert sp.suggest_cutoff(32, 32, 2, 1.0, 2.0, 0.0, 1.0, 1e9) == 7
+    # fast link: I/O never binds, every layer qualifies ((L-1) + k*t_io <= 32 holds up to L = 31)
+    assert sp.suggest_cutoff(32, 32, 1, 1.0, 0.01, 0.0, 1.0, 1e9) == 31
+    # first term binds: t_io = 20, k = 1: N*t_io = 20(L+1) <= 32 -> L = 0; (L-1) + 20 <= 32 fine
+    assert sp.suggest_cutoff(32, 32, 1, 1.0, 20.0, 0.0, 1.0, 1e9) == 0
+    # loading one expert takes longer than the whole drafting stage: nothing can be hidden
+    assert sp.suggest_cutoff(32, 32, 1, 1.0, 40.0, 0.0, 1.0, 1e9) == -1
+    # a Mixtral-8x7B-shaped expert over a ~57 GB/s link (6.2 ms) against 32 draft layers of 75 us: none
+    assert sp.suggest_cutoff(32, 32, 1, 0.075, 6.2, 0.0, 0.336, 288.0) == -1
+    lib = sp.load_library()
+    assert lib.spmoe_suggest_cutoff(0, 32, 1, 1.0, 1.0, 0.0, 1.0, 1.0, None) == 1

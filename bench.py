@@ -86,13 +86,31 @@ def run_offload(spec, args):
     t0 = time.time()
     wl = W.Workload(d=d, f=f, E=E, k=k, shared=n_shared, dtype="bf16", layers=layers, seed=0,
                     distinct=min(args.distinct, layers * E))
-    cfg = W.make_config(wl, max_tokens=T, slots=spec["slots"], cutoff_layer=args.cutoff, pred_k=pred_k)
+    cutoff_arg = -1 if args.cutoff == "auto" else int(args.cutoff)
+    cfg = W.make_config(wl, max_tokens=T, slots=spec["slots"], cutoff_layer=cutoff_arg, pred_k=pred_k)
     L = W.Loaded(wl, cfg, warm=False, keep_canonical=False)
-    dwl = W.Workload(d=d, f=f, E=1, k=1, shared=0, dtype="bf16", layers=layers, seed=1, distinct=2)
+    dwl = W.Workload(d=d, f=args.draft_ff or f, E=1, k=1, shared=0, dtype="bf16", layers=layers, seed=1, distinct=2)
     D = W.Loaded(dwl, W.make_config(dwl, max_tokens=1), keep_canonical=False)
     blob = W.sp.expert_blob_bytes(cfg)
-    log("bench: offload workload %s: %d layers, %d slots/layer, cutoff %d, sigma %.2f, pred_k %d, built in %.1f s"
-        % (args.workload, layers, spec["slots"], args.cutoff, args.sigma, pred_k, time.time() - t0))
+    # profiled inputs of the cutoff policy: per-expert load time, per-layer compute time of the drafting stage
+    dx1 = torch.zeros((1, d), dtype=torch.float32, device="cuda")
+    dy1 = torch.empty((1, d), dtype=torch.float32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for rep in range(2):
+        ev[0].record()
+        for l in range(layers):
+            D.ctx.moe_verify_layer(l, dx1, dy1)
+        ev[1].record()
+        torch.cuda.synchronize()
+    t_comp_ms = ev[0].elapsed_time(ev[1]) / layers
+    t_io_ms = L.ctx.measure_expert_load_ms(0, 0, repeats=3)
+    free_b, _total_b = torch.cuda.mem_get_info()
+    suggested = W.sp.suggest_cutoff(layers, layers, pred_k, t_comp_ms, t_io_ms, 0.0, float(blob), float(free_b))
+    cutoff = suggested if args.cutoff == "auto" else cutoff_arg
+    L.ctx.set_cutoff(cutoff)
+    log("bench: offload workload %s: %d layers, %d slots/layer, cutoff %d (policy suggests %d: t_comp %.3f ms/layer, "
+        "t_io %.3f ms/expert), sigma %.2f, pred_k %d, built in %.1f s"
+        % (args.workload, layers, spec["slots"], cutoff, suggested, t_comp_ms, t_io_ms, args.sigma, pred_k, time.time() - t0))
 
     # host link peak: one 1 GiB pinned -> device copy
     pin = torch.empty(2 ** 30, dtype=torch.uint8, pin_memory=True)
@@ -118,8 +136,13 @@ def run_offload(spec, args):
     def iteration(i):
         for j in range(T - 1):
             for l in range(layers):
-                if 0 <= l <= args.cutoff:
-                    ctx.prefetch(l, ctx.predict_experts(l, dxs[i][l][j:j + 1]))
+                if 0 <= l <= cutoff and args.prefetcher != "none":
+                    if args.prefetcher == "worker":
+                        ctx.predict_prefetch_async(l, dxs[i][l][j:j + 1])
+                    else:
+                        ctx.prefetch(l, ctx.predict_experts(l, dxs[i][l][j:j + 1]))
+                        if args.prefetcher == "blocking":
+                            ctx.sync()
                 dctx.moe_verify_layer(l, dxs[i][l][j:j + 1], dout)
         for l in range(layers):
             ctx.moe_verify_layer(l, xs[i][l], out)
@@ -139,14 +162,18 @@ def run_offload(spec, args):
 
     # profiled pass (events around every copy and every expert-GEMM launch) over a few more iterations
     n_prof = min(3, steps)
-    ctx.profile_begin()
-    dctx.profile_begin()
+    ctx.profile_begin(per_kernel=True)     # verify-layer calls wait for copies between their kernels
+    dctx.profile_begin(per_kernel=False)   # resident stand-in: one span per layer call, no events between kernels
     for i in range(n_it - n_prof, n_it):
         iteration(i)
-    recs = ctx.profile_collect(cap=200000) + dctx.profile_collect(cap=200000)
+    recs = ctx.profile_collect(cap=200000)
     pre = union([(r["t0"], r["t1"]) for r in recs if r["kind"] == 1])
     ond = union([(r["t0"], r["t1"]) for r in recs if r["kind"] == 2])
-    busy = union([(r["t0"], r["t1"]) for r in recs if r["kind"] == 4])
+    drecs = dctx.profile_collect(cap=200000)
+    # kernels executing on the compute stream: per-kernel spans of the offloaded stack, whole-call spans of the
+    # resident draft stand-in (its calls never wait for a copy)
+    busy = union([(r["t0"], r["t1"]) for r in recs if r["kind"] in (3, 4, 5, 6)] +
+                 [(r["t0"], r["t1"]) for r in drecs if r["kind"] == 0])
     copy_ms = {"prefetch": measure(pre), "ondemand": measure(ond)}
     hidden = {"prefetch": intersect(pre, busy), "ondemand": intersect(ond, busy)}
     n_pre = sum(1 for r in recs if r["kind"] == 1)
@@ -160,8 +187,9 @@ def run_offload(spec, args):
         "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "layers": layers, "d_model": d, "d_ff": f, "n_experts": E, "top_k": k,
-                   "n_shared": n_shared, "verify_tokens": T, "cache_slots_per_layer": spec["slots"], "cutoff_layer": args.cutoff,
-                   "draft_sigma": args.sigma, "pred_k": pred_k, "distinct_blobs": wl.distinct,
+                   "n_shared": n_shared, "verify_tokens": T, "cache_slots_per_layer": spec["slots"], "cutoff_layer": cutoff,
+                   "cutoff_suggested_by_policy": suggested, "t_comp_ms_per_draft_layer": t_comp_ms, "t_io_ms_per_expert": t_io_ms,
+                   "draft_sigma": args.sigma, "pred_k": pred_k, "distinct_blobs": wl.distinct, "prefetcher": args.prefetcher,
                    "draft_stage": "T-1 passes of a dense d x f SwiGLU FFN per layer (stand-in)"},
         "per_layer_verify_us_incl_stalls": ms_per_step * 1e3 / layers,
         "hit_rate": hits / max(hits + misses, 1), "cache_stats": stats,
@@ -189,9 +217,15 @@ def main():
     ap.add_argument("--resident", action="store_true",
                     help="time one layer of the workload's shape with every expert resident (compute-only number)")
     ap.add_argument("--layers", type=int, default=0, help="offload workloads: number of layers (0 = the config's)")
-    ap.add_argument("--cutoff", type=int, default=4, help="offload workloads: cutoff layer L of the prefetcher (-1 = off)")
+    ap.add_argument("--cutoff", default="4", help="offload workloads: cutoff layer L of the prefetcher (-1 = off, "
+                    "'auto' = the largest L the paper's memory/overlap constraints admit with the measured times)")
+    ap.add_argument("--draft-ff", type=int, default=0, help="offload workloads: FFN width of the dense draft-layer stand-in (0 = d_ff)")
     ap.add_argument("--sigma", type=float, default=0.1, help="offload workloads: draft-noise std")
     ap.add_argument("--pred-k", type=int, default=0, help="offload workloads: k of the predictor (0 = top_k)")
+    ap.add_argument("--prefetcher", default="worker", choices=["worker", "sync", "blocking", "none"],
+                    help="offload workloads: worker = queue tasks to the library's prefetch thread (continuous prefetching); "
+                         "sync = predict and prefetch on the caller's thread; blocking = sync + wait for the layer's copies "
+                         "before the next draft layer (layer-triggered prefetch that synchronises I/O); none = on-demand only")
     ap.add_argument("--distinct", type=int, default=32, help="offload workloads: distinct expert blobs backing the stack")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
                     help="only run N plain 1 GiB device copies (counter calibration for rocprofv3 --pmc) and exit")

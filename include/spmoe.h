@@ -87,7 +87,8 @@ typedef struct {
 /* One timed interval recorded while profiling is enabled (times in ms since spmoe_profile_begin). */
 typedef struct {
     int32_t kind;      /* 0: verify-layer span (first kernel launch to combine, waits included), 1: prefetch copy,
-                          2: on-demand copy, 3: predict, 4: one launch of the two expert GEMMs (kernels executing) */
+                          2: on-demand copy, 3: predictor kernel + its result copies, 4: one launch of the two expert
+                          GEMMs, 5: routing kernel, 6: combine kernel (3-6: kernels executing) */
     int32_t layer;
     int32_t expert;    /* copies: expert id; compute spans: number of experts launched */
     int32_t reserved;
@@ -227,10 +228,12 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* ctx, int layer, int expert,
 
 /* ---- measurement ------------------------------------------------------------------------------*/
 
-/* Starts / stops recording HIP-event timed intervals for copies and verify-layer compute spans.
+/* Starts / stops recording HIP-event timed intervals: every copy, every predictor launch and every
+ * verify-layer call; with per_kernel != 0 also every kernel launch inside the verify-layer calls (kinds
+ * 4-6 and spmoe_last_layer_kernel_ms), which puts events between the kernels and slows the layer down.
  * spmoe_profile_collect waits for the device, then writes up to cap records (in issue order) and
- * their total number.  Recording adds events to both streams; leave it off when timing throughput. */
-spmoe_status spmoe_profile_begin(spmoe_ctx* ctx);
+ * their total number.  Leave profiling off when timing throughput. */
+spmoe_status spmoe_profile_begin(spmoe_ctx* ctx, int per_kernel);
 spmoe_status spmoe_profile_collect(spmoe_ctx* ctx, spmoe_profile_record* host_out, int cap, int* host_n_out);
 
 /* Durations in ms of the kernels of the most recent spmoe_moe_verify_layer call that ran with

@@ -96,7 +96,7 @@ def load_library():
         "spmoe_predict_experts": (i32, [vp, i32, vp, i32, vp, vp]),
         "spmoe_prefetch": (i32, [vp, i32, vp, i32]),
         "spmoe_moe_verify_layer": (i32, [vp, i32, vp, i32, vp]),
-        "spmoe_profile_begin": (i32, [vp]),
+        "spmoe_profile_begin": (i32, [vp, i32]),
         "spmoe_profile_collect": (i32, [vp, vp, i32, vp]),
         "spmoe_last_layer_kernel_ms": (i32, [vp, vp]),
         "spmoe_suggest_cutoff": (i32, [i32, i32, i32, ctypes.c_double, ctypes.c_double, ctypes.c_double,
@@ -284,8 +284,8 @@ class Context:
                                                     _dev_ptr(dev_out, t.float32)), "spmoe_moe_verify_layer")
 
     # ---- measurement -------------------------------------------------------------------------------
-    def profile_begin(self):
-        self._check(self.lib.spmoe_profile_begin(self.h), "spmoe_profile_begin")
+    def profile_begin(self, per_kernel=True):
+        self._check(self.lib.spmoe_profile_begin(self.h, 1 if per_kernel else 0), "spmoe_profile_begin")
 
     def profile_collect(self, cap=65536):
         recs = (ProfileRecord * cap)()

@@ -57,6 +57,12 @@ constexpr int kLoadQueueSlots = 128;
 
 }  // namespace
 
+// Contexts that profile at the same time share one time origin, so their records can be laid on one
+// timeline: the first context to start profiling records it, the others reuse it.
+static std::mutex g_prof_mu;
+static hipEvent_t g_prof_origin = nullptr;
+static int g_prof_active = 0;
+
 struct spmoe_ctx {
     spmoe_config cfg;
     hipStream_t compute = nullptr;
@@ -94,6 +100,7 @@ struct spmoe_ctx {
 
     // profiling
     bool profiling = false;
+    bool profile_kernels = false;    // also time every kernel launch (adds events between kernels)
     hipEvent_t prof_origin = nullptr;
     std::vector<TimedSpan> spans;
     hipEvent_t kev[8] = {};          // kernel-boundary events of the last profiled verify call
@@ -163,6 +170,7 @@ int take_slot(spmoe_ctx* c, Layer& L) {
 spmoe_status span_begin(spmoe_ctx* c, hipStream_t st, int kind, int layer, int expert, size_t* id) {
     *id = (size_t)-1;
     if (!c->profiling) return SPMOE_OK;
+    if (kind >= 4 && !c->profile_kernels) return SPMOE_OK;   // per-kernel spans only on request
     TimedSpan sp{nullptr, nullptr, kind, layer, expert};
     HIP_TRY(c, hipEventCreate(&sp.begin));
     HIP_TRY(c, hipEventCreate(&sp.end));
@@ -223,7 +231,7 @@ SpmoeShape shape_of(const spmoe_ctx* c, int T) {
 }
 
 void kernel_mark(spmoe_ctx* c, int i) {
-    if (c->profiling && c->kev[i]) (void)hipEventRecord(c->kev[i], c->compute);
+    if (c->profiling && c->profile_kernels && c->kev[i]) (void)hipEventRecord(c->kev[i], c->compute);
 }
 
 // One launch of the two expert GEMMs for the experts in `list`, timed per kernel when profiling.
@@ -233,7 +241,8 @@ spmoe_status launch_experts(spmoe_ctx* c, int layer, const SpmoeShape& sh, const
     size_t busy;
     spmoe_status st = span_begin(c, c->compute, 4, layer, list.n, &busy);   // kernels really executing
     if (st != SPMOE_OK) return st;
-    if (c->profiling) {
+    const bool timed = c->profiling && c->profile_kernels;
+    if (timed) {
         HIP_TRY(c, hipEventCreate(&k2.begin));
         HIP_TRY(c, hipEventCreate(&k2.end));
         HIP_TRY(c, hipEventCreate(&k3.end));
@@ -241,9 +250,9 @@ spmoe_status launch_experts(spmoe_ctx* c, int layer, const SpmoeShape& sh, const
         HIP_TRY(c, hipEventRecord(k2.begin, c->compute));
     }
     HIP_TRY(c, spmoe_launch_gate_up(c->compute, c->cfg.weight_dtype, sh, list, c->route, x, c->h));
-    if (c->profiling) HIP_TRY(c, hipEventRecord(k2.end, c->compute));
+    if (timed) HIP_TRY(c, hipEventRecord(k2.end, c->compute));
     HIP_TRY(c, spmoe_launch_down(c->compute, c->cfg.weight_dtype, sh, list, c->route, c->h, c->ypart, c->down_splits));
-    if (c->profiling) {
+    if (timed) {
         HIP_TRY(c, hipEventRecord(k3.end, c->compute));
         c->kspans.push_back(k2);
         c->kspans.push_back(k3);
@@ -565,7 +574,10 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
     free_spans(c);
     free_kspans(c);
     for (auto& e : c->kev) if (e) (void)hipEventDestroy(e);
-    if (c->prof_origin) (void)hipEventDestroy(c->prof_origin);
+    if (c->profiling) {
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof_active -= 1;
+    }
     for (auto& L : c->layers) {
         for (auto& sl : L.slots) {
             if (sl.dev) (void)hipFree(sl.dev);
@@ -847,7 +859,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
     const int E = c->cfg.n_experts, dt = c->cfg.weight_dtype;
     const SpmoeShape sh = shape_of(c, T);
 
-    if (c->profiling) {
+    if (c->profiling && c->profile_kernels) {
         free_kspans(c);
         for (auto& e : c->kev) if (!e) HIP_TRY(c, hipEventCreate(&e));
     }
@@ -856,9 +868,14 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
     if (st != SPMOE_OK) return st;
 
     kernel_mark(c, 0);
+    size_t k1span;
+    st = span_begin(c, c->compute, 5, layer, 0, &k1span);
+    if (st != SPMOE_OK) return st;
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, dt, dev_x, L.gate, T, E, c->cfg.d_model, c->cfg.top_k,
                                       c->cfg.renorm_topk, c->route.idx, c->route.w, c->route.logits, c->cfg.n_shared,
                                       c->route.counts, c->route.offsets, c->route.perm, c->route.ticket));
+    st = span_end(c, c->compute, k1span);
+    if (st != SPMOE_OK) return st;
     kernel_mark(c, 1);
 
     SpmoeExpertList list;
@@ -938,7 +955,12 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
         }
     }
     kernel_mark(c, 2);
+    size_t k4span;
+    st = span_begin(c, c->compute, 6, layer, 0, &k4span);
+    if (st != SPMOE_OK) return st;
     HIP_TRY(c, spmoe_launch_combine(c->compute, sh, c->route, c->ypart, c->down_splits, dev_out));
+    st = span_end(c, c->compute, k4span);
+    if (st != SPMOE_OK) return st;
     kernel_mark(c, 3);
     return span_end(c, c->compute, span);
 }
@@ -994,17 +1016,27 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* c, int layer, int expert, i
 
 // ---- measurement ------------------------------------------------------------------------------------
 
-spmoe_status spmoe_profile_begin(spmoe_ctx* c) {
+spmoe_status spmoe_profile_begin(spmoe_ctx* c, int per_kernel) {
     if (!c) return SPMOE_EINVAL;
     Guard guard(c);
     if (guard.st != SPMOE_OK) return guard.st;
     free_spans(c);
-    if (!c->prof_origin) HIP_TRY(c, hipEventCreate(&c->prof_origin));
     HIP_TRY(c, hipStreamSynchronize(c->copy));
     HIP_TRY(c, hipStreamSynchronize(c->compute));
-    HIP_TRY(c, hipEventRecord(c->prof_origin, c->compute));
-    HIP_TRY(c, hipStreamWaitEvent(c->copy, c->prof_origin, 0));
+    {
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        if (!c->profiling) {
+            if (g_prof_active == 0) {
+                if (!g_prof_origin) HIP_TRY(c, hipEventCreate(&g_prof_origin));
+                HIP_TRY(c, hipEventRecord(g_prof_origin, c->compute));
+                HIP_TRY(c, hipEventSynchronize(g_prof_origin));
+            }
+            g_prof_active += 1;
+        }
+        c->prof_origin = g_prof_origin;
+    }
     c->profiling = true;
+    c->profile_kernels = per_kernel != 0;
     return SPMOE_OK;
 }
 
@@ -1013,9 +1045,14 @@ spmoe_status spmoe_profile_collect(spmoe_ctx* c, spmoe_profile_record* host_out,
     if (!host_n_out || (cap > 0 && !host_out)) return fail(c, SPMOE_EINVAL, "NULL output pointer");
     Guard guard(c);
     if (guard.st != SPMOE_OK) return guard.st;
+    if (c->profiling) {
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof_active -= 1;
+    }
     c->profiling = false;
     spmoe_status st = sync_streams(c);
     if (st != SPMOE_OK) return st;
+    if (!c->prof_origin) return fail(c, SPMOE_ESTATE, "profiling was never started");
     const int n = (int)c->spans.size();
     for (int i = 0; i < n && i < cap; ++i) {
         const TimedSpan& s = c->spans[i];

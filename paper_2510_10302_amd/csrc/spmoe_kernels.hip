@@ -95,7 +95,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 // ---------------------------------------------------------------------------------------------
 // Token -> expert grouping of T*k routed assignments (+ n_shared*T shared-expert assignments).
-// Runs inside one workgroup of 256 threads; s_idx / s_cnt / s_scan are workgroup LDS arrays.
+// Runs inside one workgroup (256 or 512 threads); s_idx / s_cnt / s_scan are workgroup LDS arrays.
 //   counts[e], offsets[e] (exclusive prefix, E_tot + 1 entries), perm = assignment ids a = t*k + r
 //   expert by expert, ascending inside an expert (a stable counting sort).  Shared expert s owns the
 //   assignments T*k + s*T + t, t = 0..T-1.
@@ -104,18 +104,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n_shared, int32_t* counts,
                                   int32_t* offsets, int32_t* perm, int* s_idx, int* s_cnt, int* s_scan) {
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, nthr = blockDim.x;
     const int A = T * k;
     const int E_tot = E + n_shared;
-    for (int e = tid; e < 2 * 256; e += 256) s_cnt[e] = 0;
+    for (int e = tid; e < 2 * 256; e += nthr) s_cnt[e] = 0;
     __syncthreads();
-    for (int a = tid; a < A; a += 256) {
+    for (int a = tid; a < A; a += nthr) {
         int e = __hip_atomic_load(idx + a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         e = min(max(e, 0), E - 1);
         s_idx[a] = e;
         atomicAdd(&s_cnt[e], 1);
     }
-    for (int s = tid; s < n_shared; s += 256) s_cnt[E + s] = T;
+    for (int s = tid; s < n_shared; s += nthr) s_cnt[E + s] = T;
     __syncthreads();
     // exclusive scan of the counts by wave 0: four consecutive experts per lane, DPP scan of the lane totals
     if (tid < 64) {
@@ -134,18 +134,18 @@ __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n
         if (tid == 0) offsets[E_tot] = A + n_shared * T;
     }
     __syncthreads();
-    for (int a = tid; a < A; a += 256) {
+    for (int a = tid; a < A; a += nthr) {
         const int e = s_idx[a];
         int rank = 0;
 #pragma unroll 8
         for (int b = 0; b < a; ++b) rank += (s_idx[b] == e);
         perm[s_scan[e] + rank] = a;
     }
-    for (int a = A + tid; a < A + n_shared * T; a += 256) perm[a] = a;
+    for (int a = A + tid; a < A + n_shared * T; a += nthr) perm[a] = a;
 }
 
 // ---------------------------------------------------------------------------------------------
-// K1: gate logits + softmax + top-k (+ grouping by the last workgroup).  Grid = T, block = 256.
+// K1: gate logits + softmax + top-k (+ grouping by the last workgroup).  Grid = T, block = 256 (512 for E >= 32).
 // ---------------------------------------------------------------------------------------------
 // Raw 8-element weight chunk (16 bytes of bf16 or 32 bytes of fp32) and its dot product with 8 x values.
 template <typename WT> struct Chunk8;
@@ -173,12 +173,13 @@ template <> struct Chunk8<float> {
     }
 };
 
-// logits[e] = sum_j x[j] * Wg[e][j] for the experts of this wave: EPW experts per pass, four waves.
+// logits[e] = sum_j x[j] * Wg[e][j] for the experts of this wave: EPW experts per pass and wave.
 template <typename WT, int EPW>
 __device__ __forceinline__ void gate_logits_pass(const float* __restrict__ xt, const WT* __restrict__ wg, int E, int d,
                                                  int wave, int lane, float* s_logit) {
     constexpr int KI = (sizeof(WT) == 2 ? 16 : 8) / EPW;      // chunks per lane and round
-    for (int e0 = wave * EPW; e0 < E; e0 += 4 * EPW) {
+    const int nwaves = blockDim.x >> 6;
+    for (int e0 = wave * EPW; e0 < E; e0 += nwaves * EPW) {
         float acc[EPW];
 #pragma unroll
         for (int q = 0; q < EPW; ++q) acc[q] = 0.f;
@@ -216,7 +217,7 @@ __device__ __forceinline__ void gate_logits_pass(const float* __restrict__ xt, c
 }
 
 template <typename WT>
-__global__ __launch_bounds__(256) void gate_topk_kernel(const float* __restrict__ x, const WT* __restrict__ wg,
+__global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict__ x, const WT* __restrict__ wg,
                                                         int T, int E, int d, int k, int renorm,
                                                         int32_t* __restrict__ idx_out, float* __restrict__ w_out,
                                                         float* __restrict__ logits_out, int do_group, int n_shared,
@@ -664,11 +665,12 @@ hipError_t spmoe_launch_gate_topk(hipStream_t stream, int dtype, const float* x,
                                   int k, int renorm, int32_t* idx, float* w, float* logits, int n_shared,
                                   int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* ticket) {
     const int do_group = counts != nullptr;
+    const int threads = (E >= 32) ? 512 : 256;
     if (dtype == SPMOE_BF16)
-        hipLaunchKernelGGL(gate_topk_kernel<uint16_t>, dim3(T), dim3(256), 0, stream, x, static_cast<const uint16_t*>(wg),
+        hipLaunchKernelGGL(gate_topk_kernel<uint16_t>, dim3(T), dim3(threads), 0, stream, x, static_cast<const uint16_t*>(wg),
                            T, E, d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket);
     else
-        hipLaunchKernelGGL(gate_topk_kernel<float>, dim3(T), dim3(256), 0, stream, x, static_cast<const float*>(wg), T, E,
+        hipLaunchKernelGGL(gate_topk_kernel<float>, dim3(T), dim3(threads), 0, stream, x, static_cast<const float*>(wg), T, E,
                            d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket);
     return hipGetLastError();
 }

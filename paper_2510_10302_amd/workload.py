@@ -20,6 +20,8 @@ CONFIGS = {
     "c2_mixtral_8x7b": dict(d=4096, f=14336, E=8,  k=2, shared=0, T=8,  dtype="bf16", layers=1,  slots=None),
     "c3_mixtral_8x7b_offload": dict(d=4096, f=14336, E=8, k=2, shared=0, T=8, dtype="bf16", layers=32, slots=3),
     "c4_deepseek_v2_lite": dict(d=2048, f=1408, E=64, k=6, shared=2, T=16, dtype="bf16", layers=26, slots=16),
+    # third model pair of the paper's Table 1 (not one of the five benchmark configurations)
+    "phi_3_5_moe": dict(d=4096, f=6400, E=16, k=2, shared=0, T=8, dtype="bf16", layers=32, slots=4),
     "c5_mixtral_8x22b": dict(d=6144, f=16384, E=8, k=2, shared=0, T=32, dtype="bf16", layers=56, slots=2),
 }
 

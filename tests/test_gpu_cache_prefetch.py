@@ -163,3 +163,28 @@ def test_measured_load_time_and_suggested_cutoff():
     assert sp.suggest_cutoff(2, 2, 1, 4 * ms, ms, 0.0, nbytes, 1e12) == 1
     assert sp.suggest_cutoff(2, 2, 1, 0.25 * ms, ms, 0.0, nbytes, 1e12) == -1
     L.close()
+
+
+def test_stress_small_budgets_random_order_async():
+    # slot hazards: 1-2 slots per layer, layers visited in random order, worker-thread prefetches racing with
+    # verify calls; every output must stay bit-identical to the all-resident run
+    import torch
+    T, n_layers = 8, 4
+    wl, ref = _setup(slots=None, cutoff=-1, layers=n_layers)
+    rng = np.random.default_rng(99)
+    plan = [(int(rng.integers(0, n_layers)), int(rng.integers(0, 50))) for _ in range(40)]
+    xs = {p: si.hidden(12, T, 256, iteration=p[1], layer=p[0]) for p in plan}
+    want = {p: gpu_layer(ref, p[0], xs[p])["out"] for p in plan}
+    ref.close()
+    for slots in (1, 2):
+        wl2, L = _setup(slots=slots, cutoff=n_layers - 1, layers=n_layers, pred_k=2)
+        for step, p in enumerate(plan):
+            nxt = plan[(step + 1) % len(plan)]
+            L.ctx.predict_prefetch_async(nxt[0], torch.from_numpy(xs[nxt][:3]).cuda())    # prefetch for a later call
+            if step % 3 == 0:
+                L.ctx.prefetch(p[0], rng.integers(0, 8, size=2).tolist())
+            got = gpu_layer(L, p[0], xs[p])["out"]
+            assert np.array_equal(got, want[p]), (slots, step, p)
+        st = L.ctx.expert_cache_stats()
+        assert st["evictions"] > 0 and st["prefetch_issued"] > 0
+        L.close()

@@ -258,3 +258,13 @@ def test_fp32_weights_mid_size_and_offload(oracle32):
             x = si.hidden(23, 20, 160, layer=layer)
             rep = check_layer(gpu_layer(L, layer, x), oracle_layer(oracle32, wl, layer, x), 2, REL_L2_F32)
         L.close()
+
+
+def test_phi_3_5_moe_layer_full_size(oracle32):
+    # the paper's third model pair (Table 1): d=4096, f=6400, 16 experts top-2; f/32 = 200 k-steps has no exact plan
+    wl = _wl(d=4096, f=6400, E=16, k=2, shared=0, dtype="bf16", layers=1, seed=0)
+    L = _loaded(wl, 8)
+    x = si.hidden(70, 8, 4096)
+    rep = check_layer(gpu_layer(L, 0, x), oracle_layer(oracle32, wl, 0, x), 2, REL_L2_BF16)
+    print("phi", rep)
+    L.close()

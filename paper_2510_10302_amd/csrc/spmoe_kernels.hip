@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
+#include <stdio.h>
 #include <stdlib.h>
 
 #include "spmoe_internal.h"
@@ -355,6 +356,7 @@ __global__ __launch_bounds__(256) void permute_kernel(const int32_t* idx, int T,
 enum { MODE_GU = 0, MODE_DOWN = 1 };
 
 #define GEMM_MAX_GROUPS (2 * SPMOE_MAX_ETOT)
+#define GEMM_MAX_ASSIGN (SPMOE_MAX_TOKENS * (SPMOE_MAX_TOPK + SPMOE_MAX_SHARED))
 
 struct GemmParams {
     const int32_t* offsets;
@@ -364,11 +366,14 @@ struct GemmParams {
     float* ypart;         // MODE_DOWN output [splits][A_tot][d]
     int32_t T, k, d, f;
     int32_t A_tot;        // T*k + n_shared*T
+    int32_t E_tot;        // routed + shared experts
     int32_t ks_total;     // k-steps of the contraction: d/32 (GU), f/32 (DOWN)
     int32_t ks_split;     // k-steps per K-split
     int32_t splits;       // K-splits
-    int32_t n_tiles;      // units along N: f/16 (GU), d/32 (DOWN)
-    int32_t waves;        // waves per workgroup
+    int32_t n_tiles;      // units along N: (f/16)/nw (GU), (d/32)/nw (DOWN)
+    int32_t waves;        // waves per workgroup = kw * nw
+    int32_t kw;           // waves that split the K range of one N sub-tile
+    int32_t nw;           // N sub-tiles a workgroup works on side by side (each kw waves)
 };
 
 // largest divisor of ksw that is <= limit (the ring must divide the per-unit step count so that ring
@@ -381,7 +386,7 @@ constexpr int ring_depth(int ksw, int limit) {
 }
 
 template <int MODE, int KSW, bool EXACT>
-__global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list,
+__global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list,
                                                                                 const GemmParams p) {
     // Two weight tiles are in flight per k-step: gate and up tile of one N-tile (adjacent KiB) in MODE_GU,
     // the tiles of two consecutive N-tiles in MODE_DOWN (ks_total KiB apart); both share the B operand.
@@ -392,13 +397,19 @@ __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(c
     extern __shared__ float s_mem[];
     float* s_red = s_mem;                                 // [2][waves][NMAT][64 lanes][4]
     int* s_grp = reinterpret_cast<int*>(s_mem + 2 * p.waves * NMAT * 256);   // [GEMM_MAX_GROUPS + 1]
+    int* s_off = s_grp + GEMM_MAX_GROUPS + 1;             // [SPMOE_MAX_ETOT + 1] copy of offsets
+    int* s_perm = s_off + SPMOE_MAX_ETOT + 1;             // [GEMM_MAX_ASSIGN] copy of perm
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kg = lane >> 4;
+    const int kslice = wave % p.kw, nsub = wave / p.kw;  // this wave's K slice and N sub-tile of the unit
     const int K = (MODE == MODE_GU) ? p.d : p.f;          // contraction length
     const int N = (MODE == MODE_GU) ? p.f : p.d;          // output features
 
-    // ---- active groups of this launch: (list entry, token tile) pairs with at least one token
+    // ---- routing tables into LDS (read again at every change of group), and the active groups of this
+    //      launch: (list entry, token tile) pairs with at least one token
+    for (int i = tid; i < p.A_tot; i += blockDim.x) s_perm[i] = p.perm[i];
+    for (int i = tid; i <= p.E_tot; i += blockDim.x) s_off[i] = p.offsets[i];
     if (wave == 0) {
         int base = 0;
         for (int i0 = 0; i0 < list.n; i0 += 64) {
@@ -435,11 +446,12 @@ __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(c
         const int g = u / upg, rem = u - g * upg;
         const int s = rem / p.n_tiles, nt = rem - s * p.n_tiles;
         const int li = s_grp[g] >> 1;
-        const int ks_lo = s * p.ks_split + wave * KSW;
+        const int ks_lo = s * p.ks_split + kslice * KSW;
         const int ks_hi = min(min(ks_lo + KSW, (s + 1) * p.ks_split), p.ks_total);
         nks = EXACT ? KSW : max(ks_hi - ks_lo, 0);
         const char* blob = static_cast<const char*>(list.blob[li]) + region;
-        const size_t tile = (MODE == MODE_GU) ? (size_t)nt : (size_t)2 * nt;   // first tile of the unit
+        const size_t sub = (size_t)nt * p.nw + nsub;                                   // this wave's sub-tile
+        const size_t tile = (MODE == MODE_GU) ? sub : 2 * sub;                        // its first weight tile
         return reinterpret_cast<const bf16x8*>(blob) + (tile * p.ks_total + ks_lo) * STEP + lane;
     };
 
@@ -470,11 +482,11 @@ __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(c
             cur_gs = g * p.splits + s;
             const int gi = s_grp[g];
             const int e = list.id[gi >> 1];
-            beg = p.offsets[e] + 16 * (gi & 1);
-            cnt = min(16, p.offsets[e + 1] - beg);
-            const int ks_lo = s * p.ks_split + wave * KSW;
-            const int a_n = (n < cnt) ? p.perm[beg + n] : -1;
-            a_out = (tid < 256 && (tid >> 4) < cnt) ? p.perm[beg + (tid >> 4)] : -1;
+            beg = s_off[e] + 16 * (gi & 1);
+            cnt = min(16, s_off[e + 1] - beg);
+            const int ks_lo = s * p.ks_split + kslice * KSW;
+            const int a_n = (n < cnt) ? s_perm[beg + n] : -1;
+            a_out = (((tid & 255) >> 4) < cnt) ? s_perm[beg + ((tid & 255) >> 4)] : -1;
             if (MODE == MODE_GU) {
                 const int routed = p.T * p.k;
                 const int tok = (a_n < 0) ? 0 : (a_n < routed ? a_n / p.k : (a_n - routed) % p.T);
@@ -539,23 +551,24 @@ __global__ __launch_bounds__((KSW > 12 ? 8 : 16) * 64) void expert_gemm_kernel(c
         for (int m = 0; m < NMAT; ++m) *reinterpret_cast<f32x4*>(red + ((wave * NMAT + m) * 64 + lane) * 4) = acc[m];
         // LDS writes done, then workgroup barrier; outstanding weight loads keep flying across it
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        // o -> (token on, feature fi), consecutive threads on consecutive features; workgroups of fewer
-        // than four waves take several outputs per thread
-        for (int o = tid; o < 256; o += blockDim.x) {
-            const int fi = o & 15, on = o >> 4;
-            if (on >= cnt) break;
-            const int a_o = (o == tid) ? a_out : p.perm[beg + on];
+        // o -> (sub-tile, token on, feature fi), consecutive threads on consecutive features; small workgroups
+        // take several outputs per thread.  The kw partial sums of a sub-tile are added in wave order.
+        for (int o = tid; o < 256 * p.nw; o += blockDim.x) {
+            const int sub = o >> 8, fi = o & 15, on = (o & 255) >> 4;
+            if (on >= cnt) continue;
+            const int a_o = (o == tid) ? a_out : s_perm[beg + on];
             const int src = (((fi >> 2) * 16 + on) * 4) + (fi & 3);
             float s0 = 0.f, s1 = 0.f;
-            for (int w = 0; w < p.waves; ++w) {
+            for (int w = sub * p.kw; w < (sub + 1) * p.kw; ++w) {
                 s0 += red[(w * NMAT) * 256 + src];
                 s1 += red[(w * NMAT + 1) * 256 + src];
             }
+            const int st = nt * p.nw + sub;               // sub-tile index along N
             if (MODE == MODE_GU) {
                 const float hval = (s0 / (1.f + expf(-s0))) * s1;
-                p.h[(size_t)a_o * N + nt * 16 + fi] = (uint16_t)f32_to_bf16_bits(hval);
+                p.h[(size_t)a_o * N + st * 16 + fi] = (uint16_t)f32_to_bf16_bits(hval);
             } else {
-                float* y = p.ypart + ((size_t)s * p.A_tot + a_o) * N + nt * 32 + fi;
+                float* y = p.ypart + ((size_t)s * p.A_tot + a_o) * N + st * 32 + fi;
                 y[0] = s0;
                 y[16] = s1;
             }
@@ -681,14 +694,14 @@ hipError_t spmoe_launch_permute(hipStream_t stream, const int32_t* idx, int T, i
     return hipGetLastError();
 }
 
-// Factorisation of the contraction's k-steps into (K-splits) x (waves) x (k-steps per wave).
+// Factorisation of a GEMM: K-splits x kw waves along K x ksw k-steps per wave, and nw N sub-tiles side by side.
 struct GemmPlan {
-    int splits, waves, ksw;
+    int splits, kw, ksw, nw;
     bool exact;
+    int waves() const { return kw * nw; }
 };
 
 static const int kExactKsw[] = {32, 28, 24, 16, 14, 12, 11, 8, 4};
-static const int kWavePreference[] = {16, 8, 11, 12, 10, 14, 4, 6, 2, 1};
 
 static bool is_exact_ksw(int ksw) {
     for (int v : kExactKsw)
@@ -696,38 +709,60 @@ static bool is_exact_ksw(int ksw) {
     return false;
 }
 
-// Workgroups of more than 8 waves leave 128 VGPRs per lane, enough for 12 k-steps of token tile.
-static bool plan_ok(int waves, int ksw) { return ksw <= 12 || waves <= 8; }
+// Workgroups of more than 8 waves leave 128 VGPRs per lane, enough for 14 k-steps of token tile.
+static bool plan_ok(int waves, int ksw) { return waves >= 1 && waves <= 16 && (ksw <= 14 || waves <= 8); }
 
-static GemmPlan plan_gemm(int ks_total, int max_splits) {
-    const char* force = getenv("SPMOE_GEMM_WAVES");   // tuning aid: preferred waves per workgroup
-    const int forced = force ? atoi(force) : 0;
-    if (forced > 0)
-        for (int splits = 1; splits <= max_splits; splits *= 2) {
-            if (ks_total % (splits * forced)) continue;
-            const int ksw = ks_total / splits / forced;
-            if (is_exact_ksw(ksw) && plan_ok(forced, ksw)) return GemmPlan{splits, forced, ksw, true};
-        }
+// ks_total: k-steps of the contraction; n_units: N-tiles (GU) or N-tile pairs (DOWN); env: optional override
+// "splits,kw,ksw,nw" (tuning aid).
+static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char* env) {
+    const char* force = getenv(env);
+    if (force) {
+        int s = 0, kw = 0, ksw = 0, nw = 0;
+        if (sscanf(force, "%d,%d,%d,%d", &s, &kw, &ksw, &nw) == 4 && s >= 1 && s <= max_splits && nw >= 1 &&
+            s * kw * ksw == ks_total && n_units % nw == 0 && is_exact_ksw(ksw) && plan_ok(kw * nw, ksw))
+            return GemmPlan{s, kw, ksw, nw, true};
+    }
+    // preference (measured, the differences are small): as few K-splits as possible, one N sub-tile, 9..16 waves
+    static const int kKswPreference[] = {12, 8, 11, 14, 16, 4, 24, 28, 32};
     for (int splits = 1; splits <= max_splits; splits *= 2) {
         if (ks_total % splits) break;
         const int per = ks_total / splits;
-        for (int waves : kWavePreference) {
-            if (per % waves) continue;
-            const int ksw = per / waves;
-            if (is_exact_ksw(ksw) && plan_ok(waves, ksw)) return GemmPlan{splits, waves, ksw, true};
+        for (int nw : {1, 2, 4}) {
+            if (n_units % nw) continue;
+            for (int ksw : kKswPreference) {
+                if (per % ksw) continue;
+                const int kw = per / ksw, waves = kw * nw;
+                if (!plan_ok(waves, ksw)) continue;
+                if (waves > 8 || (waves == 8 && ksw > 14)) return GemmPlan{splits, kw, ksw, nw, true};
+            }
         }
+    }
+    for (int splits = 1; splits <= max_splits; splits *= 2) {       // any exact plan with at least 4 waves
+        if (ks_total % splits) break;
+        const int per = ks_total / splits;
+        for (int ksw : kKswPreference) {
+            if (per % ksw) continue;
+            const int kw = per / ksw;
+            if (kw >= 4 && plan_ok(kw, ksw)) return GemmPlan{splits, kw, ksw, 1, true};
+        }
+    }
+    for (int ksw : kExactKsw) {                                      // tiny contractions: any exact plan
+        if (ks_total % ksw) continue;
+        if (plan_ok(ks_total / ksw, ksw)) return GemmPlan{1, ks_total / ksw, ksw, 1, true};
     }
     // generic instance: up to 8 waves of at most 32 k-steps each, more K-splits for longer contractions
     int splits = 1;
     while ((ks_total + splits - 1) / splits > 8 * 32) ++splits;
     const int per = (ks_total + splits - 1) / splits;
-    return GemmPlan{splits, (per + 31) / 32, 32, false};
+    return GemmPlan{splits, (per + 31) / 32, 32, 1, false};
 }
 
+static GemmPlan plan_gate_up(int d, int f) { return plan_gemm(d / 32, f / 16, 1, "SPMOE_PLAN_GATE_UP"); }
+static GemmPlan plan_down(int d, int f) { return plan_gemm(f / 32, d / 32, 4, "SPMOE_PLAN_DOWN"); }
+
 int spmoe_down_splits(int dtype, int d, int f) {
-    (void)d;
     if (dtype != SPMOE_BF16) return 1;
-    return plan_gemm(f / 32, 4).splits;
+    return plan_down(d, f).splits;
 }
 
 // Persistent grid size: as many workgroups as fit on the chip at once for this instance.
@@ -746,14 +781,14 @@ static int resident_blocks(Kernel kernel, int threads, size_t lds) {
 template <int MODE>
 static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, const SpmoeExpertList& list,
                                    const GemmParams& p) {
-    const int threads = plan.waves * 64;
-    const size_t lds = (size_t)2 * plan.waves * 2 * 256 * sizeof(float) +
-                       (GEMM_MAX_GROUPS + 1) * sizeof(int);
+    const int threads = plan.waves() * 64;
+    const size_t lds = (size_t)2 * plan.waves() * 2 * 256 * sizeof(float) +
+                       (GEMM_MAX_GROUPS + 1 + SPMOE_MAX_ETOT + 1 + GEMM_MAX_ASSIGN) * sizeof(int);
     // cache of grid sizes per (instance, waves): [exact ksw index or generic][waves]
     static int grid_cache[2][16][17];
 #define SPMOE_GEMM_CASE(SLOT_, KSW_, EXACT_)                                                                    \
     {                                                                                                           \
-        int& g = grid_cache[MODE][SLOT_][plan.waves];                                                           \
+        int& g = grid_cache[MODE][SLOT_][plan.waves()];                                                           \
         if (g == 0) g = resident_blocks(expert_gemm_kernel<MODE, KSW_, EXACT_>, threads, lds);                  \
         hipLaunchKernelGGL((expert_gemm_kernel<MODE, KSW_, EXACT_>), dim3(g), dim3(threads), lds, stream, list, p); \
     }
@@ -786,8 +821,9 @@ static GemmParams make_params(const SpmoeShape& s, const SpmoeRouting& r) {
     p.ypart = nullptr;
     p.T = s.T; p.k = s.k; p.d = s.d; p.f = s.f;
     p.A_tot = s.T * s.k + s.n_shared * s.T;
+    p.E_tot = s.E + s.n_shared;
     p.ks_total = 0; p.ks_split = 0; p.splits = 1; p.n_tiles = 0;
-    p.waves = 4;
+    p.waves = 4; p.kw = 4; p.nw = 1;
     return p;
 }
 
@@ -798,12 +834,12 @@ hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape&
     p.x = x;
     p.h = static_cast<uint16_t*>(h);
     if (dtype == SPMOE_BF16) {
-        const GemmPlan plan = plan_gemm(s.d / 32, 1);
+        const GemmPlan plan = plan_gate_up(s.d, s.f);
         p.ks_total = s.d / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
         p.splits = plan.splits;
-        p.n_tiles = s.f / 16;
-        p.waves = plan.waves;
+        p.n_tiles = s.f / 16 / plan.nw;
+        p.waves = plan.waves(); p.kw = plan.kw; p.nw = plan.nw;
         return launch_gemm_bf16<MODE_GU>(stream, plan, list, p);
     }
     hipLaunchKernelGGL(expert_gemm_f32_kernel<MODE_GU>, dim3((s.f + 3) / 4, list.n), dim3(256), 0, stream, list, p,
@@ -818,13 +854,13 @@ hipError_t spmoe_launch_down(hipStream_t stream, int dtype, const SpmoeShape& s,
     p.h = static_cast<uint16_t*>(const_cast<void*>(h));
     p.ypart = ypart;
     if (dtype == SPMOE_BF16) {
-        const GemmPlan plan = plan_gemm(s.f / 32, 4);
+        const GemmPlan plan = plan_down(s.d, s.f);
         if (plan.splits != splits) return hipErrorInvalidValue;
         p.ks_total = s.f / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
         p.splits = plan.splits;
-        p.n_tiles = s.d / 32;
-        p.waves = plan.waves;
+        p.n_tiles = s.d / 32 / plan.nw;
+        p.waves = plan.waves(); p.kw = plan.kw; p.nw = plan.nw;
         return launch_gemm_bf16<MODE_DOWN>(stream, plan, list, p);
     }
     hipLaunchKernelGGL(expert_gemm_f32_kernel<MODE_DOWN>, dim3((s.d + 3) / 4, list.n), dim3(256), 0, stream, list, p,

@@ -216,6 +216,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--resident", action="store_true",
                     help="time one layer of the workload's shape with every expert resident (compute-only number)")
+    ap.add_argument("--tokens", type=int, default=0, help="verification batch size T (0 = the workload's)")
+    ap.add_argument("--slots", type=int, default=0, help="offload workloads: cache slots per layer (0 = the workload's)")
     ap.add_argument("--layers", type=int, default=0, help="offload workloads: number of layers (0 = the config's)")
     ap.add_argument("--cutoff", default="4", help="offload workloads: cutoff layer L of the prefetcher (-1 = off, "
                     "'auto' = the largest L the paper's memory/overlap constraints admit with the measured times)")
@@ -254,6 +256,10 @@ def main():
         print(json.dumps({"calibrate_copy": args.calibrate_copy, "bytes_read": 2 ** 30, "bytes_written": 2 ** 30}))
         return
     spec = dict(W.CONFIGS[args.workload])
+    if args.tokens:
+        spec["T"] = args.tokens
+    if args.slots and spec["slots"]:
+        spec["slots"] = args.slots
     if spec["slots"] and not args.resident:
         run_offload(spec, args)
         return

@@ -97,3 +97,17 @@ def test_cutoff_policy_hand_worked(sp):
     assert sp.suggest_cutoff(32, 32, 1, 0.075, 6.2, 0.0, 0.336, 288.0) == -1
     lib = sp.load_library()
     assert lib.spmoe_suggest_cutoff(0, 32, 1, 1.0, 1.0, 0.0, 1.0, 1.0, None) == 1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_no_cpu_fallback_when_the_library_is_missing(sp, monkeypatch):
+    from paper_2510_10302_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", os.path.join(ROOT, "does_not_exist", "libspmoe.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()

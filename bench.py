@@ -152,6 +152,8 @@ def run_offload(spec, args):
         iteration(i)
     torch.cuda.synchronize()
     st0 = ctx.expert_cache_stats()
+    if args.copy_log:
+        ctx.profile_begin(log_only=True)
     t_start = time.perf_counter()
     for i in range(warmup, n_it):
         iteration(i)
@@ -159,6 +161,15 @@ def run_offload(spec, args):
     elapsed = time.perf_counter() - t_start
     st1 = ctx.expert_cache_stats()
     stats = {key: st1[key] - st0[key] for key in st1}
+    if args.copy_log:
+        kinds = [r["kind"] for r in ctx.profile_collect(cap=500000) if r["kind"] in (1, 2)]
+        json.dump({"blob_bytes": blob, "copy_kinds_in_issue_order": kinds, "iterations": steps}, open(args.copy_log, "w"))
+        log("bench: wrote %d copy labels to %s" % (len(kinds), args.copy_log))
+        L.close()
+        D.close()
+        print(json.dumps({"metric": "moe_verify_stack_tokens_per_s", "value": T * steps / elapsed, "unit": "tokens/s",
+                          "ms_per_step": elapsed * 1e3 / steps, "copy_log": args.copy_log, "cache_stats": stats}), flush=True)
+        return
 
     # profiled pass (events around every copy and every expert-GEMM launch) over a few more iterations
     n_prof = min(3, steps)
@@ -229,6 +240,9 @@ def main():
                          "sync = predict and prefetch on the caller's thread; blocking = sync + wait for the layer's copies "
                          "before the next draft layer (layer-triggered prefetch that synchronises I/O); none = on-demand only")
     ap.add_argument("--distinct", type=int, default=32, help="offload workloads: distinct expert blobs backing the stack")
+    ap.add_argument("--copy-log", default="", metavar="PATH",
+                    help="offload workloads: instead of the HIP-event pass, log the kind (1 prefetch, 2 on-demand) of every "
+                         "expert copy of the timed iterations, in issue order, to PATH (labels for a rocprofv3 copy trace)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="N",
                     help="only run N plain 1 GiB device copies (counter calibration for rocprofv3 --pmc) and exit")
     args = ap.parse_args()

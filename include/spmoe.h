@@ -228,12 +228,15 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* ctx, int layer, int expert,
 
 /* ---- measurement ------------------------------------------------------------------------------*/
 
-/* Starts / stops recording HIP-event timed intervals: every copy, every predictor launch and every
- * verify-layer call; with per_kernel != 0 also every kernel launch inside the verify-layer calls (kinds
- * 4-6 and spmoe_last_layer_kernel_ms), which puts events between the kernels and slows the layer down.
- * spmoe_profile_collect waits for the device, then writes up to cap records (in issue order) and
- * their total number.  Leave profiling off when timing throughput. */
-spmoe_status spmoe_profile_begin(spmoe_ctx* ctx, int per_kernel);
+/* Starts recording one record per copy, predictor launch and verify-layer call, in issue order.
+ *   mode 0: each record is timed with a pair of HIP events on its stream;
+ *   mode 1: as 0, plus every kernel launch inside the verify-layer calls (kinds 4-6, and
+ *           spmoe_last_layer_kernel_ms), which puts events between the kernels and slows the layer down;
+ *   mode 2: no events at all: the records only log kind / layer / expert in issue order (times are 0),
+ *           e.g. to label the copies of an external trace.
+ * spmoe_profile_collect waits for the device, then writes up to cap records and their total number.
+ * Leave profiling off when timing throughput. */
+spmoe_status spmoe_profile_begin(spmoe_ctx* ctx, int mode);
 spmoe_status spmoe_profile_collect(spmoe_ctx* ctx, spmoe_profile_record* host_out, int cap, int* host_n_out);
 
 /* Durations in ms of the kernels of the most recent spmoe_moe_verify_layer call that ran with

@@ -284,8 +284,9 @@ class Context:
                                                     _dev_ptr(dev_out, t.float32)), "spmoe_moe_verify_layer")
 
     # ---- measurement -------------------------------------------------------------------------------
-    def profile_begin(self, per_kernel=True):
-        self._check(self.lib.spmoe_profile_begin(self.h, 1 if per_kernel else 0), "spmoe_profile_begin")
+    def profile_begin(self, per_kernel=True, log_only=False):
+        mode = 2 if log_only else (1 if per_kernel else 0)
+        self._check(self.lib.spmoe_profile_begin(self.h, mode), "spmoe_profile_begin")
 
     def profile_collect(self, cap=65536):
         recs = (ProfileRecord * cap)()

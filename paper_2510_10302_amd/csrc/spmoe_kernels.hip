@@ -775,9 +775,7 @@ static int resident_blocks(Kernel kernel, int threads, size_t lds) {
         (void)hipGetLastError();
         per_cu = 1;
     }
-    const char* mult = getenv("SPMOE_GEMM_GRID_MULT");   // tuning aid: more workgroups than fit at once
-    const int m = mult ? atoi(mult) : 1;
-    return cus * per_cu * (m >= 1 && m <= 64 ? m : 1);
+    return cus * per_cu;
 }
 
 template <int MODE>

@@ -101,6 +101,7 @@ struct spmoe_ctx {
     // profiling
     bool profiling = false;
     bool profile_kernels = false;    // also time every kernel launch (adds events between kernels)
+    bool profile_log_only = false;   // keep the records (kind, layer, expert, issue order) but record no events
     hipEvent_t prof_origin = nullptr;
     std::vector<TimedSpan> spans;
     hipEvent_t kev[8] = {};          // kernel-boundary events of the last profiled verify call
@@ -172,15 +173,17 @@ spmoe_status span_begin(spmoe_ctx* c, hipStream_t st, int kind, int layer, int e
     if (!c->profiling) return SPMOE_OK;
     if (kind >= 4 && !c->profile_kernels) return SPMOE_OK;   // per-kernel spans only on request
     TimedSpan sp{nullptr, nullptr, kind, layer, expert};
-    HIP_TRY(c, hipEventCreate(&sp.begin));
-    HIP_TRY(c, hipEventCreate(&sp.end));
-    HIP_TRY(c, hipEventRecord(sp.begin, st));
+    if (!c->profile_log_only) {
+        HIP_TRY(c, hipEventCreate(&sp.begin));
+        HIP_TRY(c, hipEventCreate(&sp.end));
+        HIP_TRY(c, hipEventRecord(sp.begin, st));
+    }
     c->spans.push_back(sp);
     *id = c->spans.size() - 1;
     return SPMOE_OK;
 }
 spmoe_status span_end(spmoe_ctx* c, hipStream_t st, size_t id) {
-    if (id == (size_t)-1) return SPMOE_OK;
+    if (id == (size_t)-1 || c->profile_log_only) return SPMOE_OK;
     HIP_TRY(c, hipEventRecord(c->spans[id].end, st));
     return SPMOE_OK;
 }
@@ -269,7 +272,10 @@ void free_kspans(spmoe_ctx* c) {
 }
 
 void free_spans(spmoe_ctx* c) {
-    for (auto& s : c->spans) { (void)hipEventDestroy(s.begin); (void)hipEventDestroy(s.end); }
+    for (auto& s : c->spans) {
+        if (s.begin) (void)hipEventDestroy(s.begin);
+        if (s.end) (void)hipEventDestroy(s.end);
+    }
     c->spans.clear();
 }
 
@@ -1016,7 +1022,7 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* c, int layer, int expert, i
 
 // ---- measurement ------------------------------------------------------------------------------------
 
-spmoe_status spmoe_profile_begin(spmoe_ctx* c, int per_kernel) {
+spmoe_status spmoe_profile_begin(spmoe_ctx* c, int mode) {
     if (!c) return SPMOE_EINVAL;
     Guard guard(c);
     if (guard.st != SPMOE_OK) return guard.st;
@@ -1036,7 +1042,8 @@ spmoe_status spmoe_profile_begin(spmoe_ctx* c, int per_kernel) {
         c->prof_origin = g_prof_origin;
     }
     c->profiling = true;
-    c->profile_kernels = per_kernel != 0;
+    c->profile_kernels = mode == 1;
+    c->profile_log_only = mode == 2;
     return SPMOE_OK;
 }
 
@@ -1057,8 +1064,10 @@ spmoe_status spmoe_profile_collect(spmoe_ctx* c, spmoe_profile_record* host_out,
     for (int i = 0; i < n && i < cap; ++i) {
         const TimedSpan& s = c->spans[i];
         float b = 0.f, e = 0.f;
-        HIP_TRY(c, hipEventElapsedTime(&b, c->prof_origin, s.begin));
-        HIP_TRY(c, hipEventElapsedTime(&e, c->prof_origin, s.end));
+        if (s.begin && s.end) {
+            HIP_TRY(c, hipEventElapsedTime(&b, c->prof_origin, s.begin));
+            HIP_TRY(c, hipEventElapsedTime(&e, c->prof_origin, s.end));
+        }
         host_out[i] = spmoe_profile_record{s.kind, s.layer, s.expert, 0, b, e};
     }
     *host_n_out = n;

@@ -248,7 +248,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on one GPU only (the path would shard by expert across GPUs, "
-            "see DESIGN.md); --gpus %d is not supported" % args.gpus)
+            "each GPU would own a subset of the experts, their cache slots and its own host link); --gpus %d is not supported" % args.gpus)
         sys.exit(2)
 
     import numpy as np

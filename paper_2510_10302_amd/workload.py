@@ -1,4 +1,4 @@
-"""Synthetic SP-MoE workloads (the shapes of BASELINE's five configurations) laid out for the library.
+"""Synthetic SP-MoE workloads (the five benchmark configurations: a small fp32 layer, Mixtral-8x7B, DeepSeek-V2-Lite and Mixtral-8x22B shapes) laid out for the library.
 
 This is plumbing around the C ABI for the tests, the smoke check and the benchmark: it draws seeded
 tensors from ``spmoe_inputs``, packs experts into pinned host blobs (``spmoe_pack_expert``), uploads

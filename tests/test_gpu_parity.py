@@ -19,7 +19,7 @@ def _wl(**kw):
 
 
 def test_c1_small_fp32(oracle32, oracle64):
-    # BASELINE config 1: d_model 512, d_ff 1024, 8 experts top-2, 5 tokens, fp32 weights, seed 0, all resident
+    # benchmark configuration 1: d_model 512, d_ff 1024, 8 experts top-2, 5 tokens, fp32 weights, seed 0, all resident
     wl = _wl(d=512, f=1024, E=8, k=2, shared=0, dtype="f32", layers=1, seed=0)
     L = _loaded(wl, 5)
     x = si.hidden(0, 5, 512)
@@ -48,7 +48,7 @@ def test_mid_size_bf16_full_compare(d, f, E, k, shared, T, oracle32):
 
 
 def test_c2_mixtral_layer_full_size(oracle32):
-    # BASELINE config 2 in the configuration bench.py times: d=4096, f=14336, 8 experts top-2, bf16, 8 tokens
+    # benchmark configuration 2 in the configuration bench.py times: d=4096, f=14336, 8 experts top-2, bf16, 8 tokens
     wl = _wl(d=4096, f=14336, E=8, k=2, shared=0, dtype="bf16", layers=1, seed=0)
     L = _loaded(wl, 8)
     x = si.hidden(0, 8, 4096)
@@ -167,7 +167,7 @@ def test_gate_topk_many_tokens_bit_exact(oracle32):
 
 
 def test_c4_deepseek_layer_full_size(oracle32):
-    # BASELINE config 4 layer shape: d=2048, f=1408, 64 routed experts top-6 + 2 shared, bf16, 16 tokens
+    # benchmark configuration 4 layer shape: d=2048, f=1408, 64 routed experts top-6 + 2 shared, bf16, 16 tokens
     wl = _wl(d=2048, f=1408, E=64, k=6, shared=2, dtype="bf16", layers=1, seed=0)
     L = _loaded(wl, 16)
     for it in range(2):
@@ -178,7 +178,7 @@ def test_c4_deepseek_layer_full_size(oracle32):
 
 
 def test_c5_mixtral_8x22b_layer_full_size(oracle32):
-    # BASELINE config 5 layer shape: d=6144, f=16384, 8 experts top-2, bf16, 32 tokens (4 sequences x 8)
+    # benchmark configuration 5 layer shape: d=6144, f=16384, 8 experts top-2, bf16, 32 tokens (4 sequences x 8)
     wl = _wl(d=6144, f=16384, E=8, k=2, shared=0, dtype="bf16", layers=1, seed=0)
     L = _loaded(wl, 32)
     x = si.hidden(50, 32, 6144)
@@ -190,7 +190,7 @@ def test_c5_mixtral_8x22b_layer_full_size(oracle32):
 
 
 def test_c3_offloaded_stack_teacher_forced(oracle32):
-    # BASELINE config 3 (reduced to 3 layers, aliased backing): Mixtral-8x7B layers, experts in pinned host
+    # benchmark configuration 3 (reduced to 3 layers, aliased backing): Mixtral-8x7B layers, experts in pinned host
     # memory, 3 cache slots per layer, draft noise sigma 0.5, cutoff layer 1; each layer is fed seeded x_l.
     import torch
     from paper_2510_10302_amd import workload as W
@@ -268,3 +268,30 @@ def test_phi_3_5_moe_layer_full_size(oracle32):
     rep = check_layer(gpu_layer(L, 0, x), oracle_layer(oracle32, wl, 0, x), 2, REL_L2_BF16)
     print("phi", rep)
     L.close()
+
+
+def test_random_shapes_against_oracle(oracle32):
+    # seeded random small shapes: ragged k-step counts, any E / k / shared / T inside the limits, resident or offloaded
+    from paper_2510_10302_amd import workload as W
+    rng = np.random.default_rng(2024)
+    checked = 0
+    for trial in range(28):
+        d = 32 * int(rng.integers(1, 17))
+        f = 32 * int(rng.integers(1, 17))
+        E = int(rng.integers(1, 25))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        shared = int(rng.integers(0, 3))
+        T = int(rng.integers(1, 33))
+        dtype = "f32" if trial % 7 == 6 else "bf16"
+        slots = None if trial % 3 else int(rng.integers(1, E + 1))
+        wl = W.Workload(d=d, f=f, E=E, k=k, shared=shared, dtype=dtype, layers=1, seed=100 + trial, gate_std=0.05, std=0.05)
+        L = W.Loaded(wl, W.make_config(wl, max_tokens=T, slots=slots, cutoff_layer=0), warm=slots is None)
+        x = si.hidden(100 + trial, T, d)
+        if slots is not None:
+            L.ctx.prefetch(0, rng.integers(0, E, size=2).tolist())
+        g = gpu_layer(L, 0, x)
+        ref = oracle_layer(oracle32, wl, 0, x)
+        rep = check_layer(g, ref, k, REL_L2_F32 if dtype == "f32" else REL_L2_BF16)
+        checked += rep["exact"] + len(rep["near_ties"])
+        L.close()
+    assert checked > 300

@@ -126,7 +126,7 @@ def test_token_order_equivariance(oracle32):
 
 
 def test_fp32_oracle_close_to_fp64_on_small_config(oracle32, oracle64):
-    # BASELINE config 1: d_model 512, d_ff 1024, 8 experts, top-2, 5 tokens, fp32 weights, seed 0
+    # benchmark configuration 1: d_model 512, d_ff 1024, 8 experts, top-2, 5 tokens, fp32 weights, seed 0
     T, d, f, E, k = 5, 512, 1024, 8, 2
     x = si.hidden(0, T, d)
     wgate = si.gate_weights(0, 0, E, d, "f32")

@@ -306,16 +306,17 @@ __global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict_
     }
     if (!do_group) return;
 
-    // ---- the last workgroup to arrive groups all assignments by expert
-    __threadfence();
-    __syncthreads();
+    // ---- the last workgroup to arrive groups all assignments by expert.  Thread 0 wrote this token's idx / w,
+    //      so it alone releases them (device-scope fence) before taking a ticket; the last workgroup reads every
+    //      token's idx with device-scope atomic loads after thread 0's acquire fence and the barrier.
     if (tid == 0) {
+        __threadfence();
         const int old = atomicAdd(ticket, 1);
         s_last = (old == T - 1);
+        __threadfence();
     }
     __syncthreads();
     if (!s_last) return;
-    __threadfence();
     group_assignments(idx_out, T, k, E, n_shared, counts, offsets, perm, s_idx, s_cnt, s_scan);
     if (tid == 0) *ticket = 0;
 }

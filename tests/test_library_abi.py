@@ -111,3 +111,19 @@ def test_no_cpu_fallback_when_the_library_is_missing(sp, monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", os.path.join(ROOT, "does_not_exist", "libspmoe.so"))
     with pytest.raises(ImportError):
         binding.load_library()
+
+
+def test_header_is_plain_c_and_cpp(tmp_path):
+    # the boundary is a C ABI: the header must compile as strict C99 and as C++ with no extra includes
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    src = ('#include "spmoe.h"\n'
+           'int main(void) { spmoe_config c; spmoe_stats s; spmoe_profile_record r; (void)c; (void)s; (void)r;\n'
+           '  return (int)sizeof(spmoe_status) + SPMOE_MAX_TOKENS * 0; }\n')
+    c_file, cpp_file = tmp_path / "abi.c", tmp_path / "abi.cpp"
+    c_file.write_text(src)
+    cpp_file.write_text(src)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-c", str(c_file),
+                           "-o", str(tmp_path / "abi_c.o")])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-c", str(cpp_file),
+                           "-o", str(tmp_path / "abi_cpp.o")])

@@ -126,7 +126,8 @@ def run_offload(spec, args):
     del pin, dev
 
     n_it = warmup + steps
-    xs = [[torch.from_numpy(si.hidden(7, T, d, iteration=i, layer=l)).cuda() for l in range(layers)] for i in range(n_it)]
+    xs = [[torch.from_numpy(si.hidden_correlated(7, T, d, args.token_corr, args.sequences, iteration=i, layer=l)).cuda()
+           for l in range(layers)] for i in range(n_it)]
     dxs = [[xs[i][l] + torch.from_numpy(si.draft_noise(7, T, d, args.sigma, iteration=i, layer=l)).cuda()
             for l in range(layers)] for i in range(n_it)]
     out = torch.empty((T, d), dtype=torch.float32, device="cuda")
@@ -200,7 +201,7 @@ def run_offload(spec, args):
         "config": {"workload": args.workload, "layers": layers, "d_model": d, "d_ff": f, "n_experts": E, "top_k": k,
                    "n_shared": n_shared, "verify_tokens": T, "cache_slots_per_layer": spec["slots"], "cutoff_layer": cutoff,
                    "cutoff_suggested_by_policy": suggested, "t_comp_ms_per_draft_layer": t_comp_ms, "t_io_ms_per_expert": t_io_ms,
-                   "draft_sigma": args.sigma, "pred_k": pred_k, "distinct_blobs": wl.distinct, "prefetcher": args.prefetcher,
+                   "draft_sigma": args.sigma, "pred_k": pred_k, "token_corr": args.token_corr, "sequences": args.sequences, "distinct_blobs": wl.distinct, "prefetcher": args.prefetcher,
                    "draft_stage": "T-1 passes of a dense d x f SwiGLU FFN per layer (stand-in)"},
         "per_layer_verify_us_incl_stalls": ms_per_step * 1e3 / layers,
         "hit_rate": hits / max(hits + misses, 1), "cache_stats": stats,
@@ -227,6 +228,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--resident", action="store_true",
                     help="time one layer of the workload's shape with every expert resident (compute-only number)")
+    ap.add_argument("--token-corr", type=float, default=0.0, metavar="RHO",
+                    help="correlation of the tokens of a sequence (x_t = rho*b_seq + sqrt(1-rho^2)*eps_t); 0 = independent")
+    ap.add_argument("--sequences", type=int, default=1, help="sequences the verification batch is split into (with --token-corr)")
     ap.add_argument("--tokens", type=int, default=0, help="verification batch size T (0 = the workload's)")
     ap.add_argument("--slots", type=int, default=0, help="offload workloads: cache slots per layer (0 = the workload's)")
     ap.add_argument("--layers", type=int, default=0, help="offload workloads: number of layers (0 = the config's)")
@@ -288,7 +292,7 @@ def main():
                                                                        W.sp.expert_blob_bytes(cfg) / 2 ** 20))
     ctx = L.ctx
     elem = 2 if spec["dtype"] == "bf16" else 4
-    xs_host = [si.hidden(1000 + i, T, d) for i in range(args.batches)]
+    xs_host = [si.hidden_correlated(1000 + i, T, d, args.token_corr, args.sequences) for i in range(args.batches)]
     xs = [torch.from_numpy(x).cuda() for x in xs_host]
     out = torch.empty((T, d), dtype=torch.float32, device="cuda")
 
@@ -353,7 +357,8 @@ def main():
         "dtype": spec["dtype"],
         "data": "synthetic",
         "config": {"workload": args.workload, "d_model": d, "d_ff": f, "n_experts": E, "top_k": k, "n_shared": n_shared,
-                   "verify_tokens": T, "experts_resident": True, "mean_active_experts": float(np.mean(e_act))},
+                   "verify_tokens": T, "experts_resident": True, "mean_active_experts": float(np.mean(e_act)),
+                   "token_corr": args.token_corr, "sequences": args.sequences},
         "kernels_ms": {"route": float(kms[0]), "gate_up": float(kms[1]), "down": float(kms[2]), "combine": float(kms[3])},
         "expert_gemm_gbs": {"gate_up": gu_gbs, "down": dn_gbs, "both": both_gbs},
         "roofline": {"bound": "hbm", "kernel": "expert_gemm_kernel<gate_up>", "achieved": gu_gbs, "peak": HBM_PEAK_GBS,

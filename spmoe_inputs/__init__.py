@@ -102,6 +102,17 @@ def hidden(seed, T, d, iteration=0, layer=0):
     return normal_f32(seed, STREAM_X + iteration * 4096 + layer, T * d).reshape(T, d)
 
 
+def hidden_correlated(seed, T, d, rho, n_seq=1, iteration=0, layer=0):
+    """x[T][d] fp32 with unit variance whose rows share a per-sequence component:
+    x_t = rho * b_seq(t) + sqrt(1 - rho^2) * eps_t, T split evenly into n_seq sequences.  rho = 0 gives hidden().
+    Neighbouring tokens of a sequence then tend to pick the same experts (the paper's Observation I)."""
+    eps = hidden(seed, T, d, iteration=iteration, layer=layer)
+    base = normal_f32(seed, STREAM_X + (1 << 36) + iteration * 4096 + layer, n_seq * d).reshape(n_seq, d)
+    per = (T + n_seq - 1) // n_seq
+    seq = np.minimum(np.arange(T) // per, n_seq - 1)
+    return (np.float32(rho) * base[seq] + np.float32(np.sqrt(1.0 - rho * rho)) * eps).astype(np.float32)
+
+
 def draft_noise(seed, T, d, sigma, iteration=0, layer=0):
     """sigma * eps[T][d]: the additive noise that turns a target hidden state into a stand-in draft one."""
     return normal_f32(seed, STREAM_NOISE + iteration * 4096 + layer, T * d, std=sigma).reshape(T, d)

@@ -38,3 +38,14 @@ def test_layout_shapes():
     assert g.shape == (96, 64) and u.shape == (96, 64) and dn.shape == (64, 96) and g.dtype == np.uint16
     assert si.gate_weights(0, 0, 8, 64, "f32").shape == (8, 64)
     assert si.hidden(0, 5, 64).shape == (5, 64)
+
+
+def test_correlated_tokens_share_a_sequence_component():
+    x0 = si.hidden_correlated(5, 32, 4096, 0.0, 4)
+    assert np.array_equal(x0, si.hidden(5, 32, 4096))
+    x = si.hidden_correlated(5, 32, 4096, 0.8, 4).astype(np.float64)
+    assert abs(x.std() - 1.0) < 2e-2
+    c = np.corrcoef(x)
+    same = np.mean([c[i, j] for i in range(32) for j in range(32) if i != j and i // 8 == j // 8])
+    other = np.mean([c[i, j] for i in range(32) for j in range(32) if i // 8 != j // 8])
+    assert abs(same - 0.64) < 0.03 and abs(other) < 0.03          # rho^2 inside a sequence, 0 across

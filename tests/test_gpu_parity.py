@@ -38,16 +38,18 @@ def test_c1_small_fp32(oracle32, oracle64):
     (1024, 8192, 2, 1, 0, 3),     # long contraction in the down projection: generic plan with K-splits
     (64, 64, 1, 1, 0, 1),         # a single expert, a single token
 ])
-def test_mid_size_bf16_full_compare(d, f, E, k, shared, T, oracle32):
+def test_mid_size_bf16_full_compare(d, f, E, k, shared, T, oracle32, oracle64):
     wl = _wl(d=d, f=f, E=E, k=k, shared=shared, dtype="bf16", layers=1, seed=3, gate_std=0.05, std=0.05)
     L = _loaded(wl, T)
     x = si.hidden(3, T, d)
-    rep = check_layer(gpu_layer(L, 0, x), oracle_layer(oracle32, wl, 0, x), k, REL_L2_BF16)
+    g = gpu_layer(L, 0, x)
+    rep = check_layer(g, oracle_layer(oracle32, wl, 0, x), k, REL_L2_BF16)
+    assert rel_l2(g["out"], oracle_layer(oracle64, wl, 0, x)["out"]) < REL_L2_BF16       # and against the fp64 build
     print((d, f, E, k, shared, T), rep)
     L.close()
 
 
-def test_c2_mixtral_layer_full_size(oracle32):
+def test_c2_mixtral_layer_full_size(oracle32, oracle64):
     # benchmark configuration 2 in the configuration bench.py times: d=4096, f=14336, 8 experts top-2, bf16, 8 tokens
     wl = _wl(d=4096, f=14336, E=8, k=2, shared=0, dtype="bf16", layers=1, seed=0)
     L = _loaded(wl, 8)
@@ -59,6 +61,10 @@ def test_c2_mixtral_layer_full_size(oracle32):
     # per-token error as well: no single token may hide behind the aggregate
     for t in range(8):
         assert rel_l2(g["out"][t], ref["out"][t]) < REL_L2_BF16
+    # sampled outputs against the fp64 build of the oracle (two tokens, computed one by one)
+    for t in (0, 5):
+        r64 = oracle64.moe_layer(x[t:t + 1], wl.gate[0], wl.layer_experts(0), 2)
+        assert np.array_equal(r64["idx"][0], g["idx"][t]) and rel_l2(g["out"][t], r64["out"][0]) < REL_L2_BF16
     L.close()
 
 
@@ -295,3 +301,30 @@ def test_random_shapes_against_oracle(oracle32):
         checked += rep["exact"] + len(rep["near_ties"])
         L.close()
     assert checked > 300
+
+
+def test_near_ties_are_listed_not_counted(oracle32, oracle64):
+    # two gate rows that differ by 1e-7 in one element give logits closer than 1e-5: whichever of the two the
+    # GPU's summation order prefers, the token must be classified as a near-tie (or match), never as a mismatch
+    import torch
+    from paper_2510_10302_amd import workload as W
+    wl = _wl(d=512, f=64, E=8, k=2, shared=0, dtype="f32", layers=1, seed=31, gate_std=0.05, std=0.05)
+    wl.gate[0][5] = wl.gate[0][1]
+    wl.gate[0][5, 17] += np.float32(1e-7)
+    L = _loaded(wl, 32)
+    near_total = exact_total = 0
+    for it in range(4):
+        x = si.hidden(31, 32, 512, iteration=it)
+        g = gpu_layer(L, 0, x)
+        ref_logits = oracle32.gate_logits(x, wl.gate[0])
+        ref_idx, _ = oracle32.route(ref_logits, 2)
+        exact, near, bad = routing_report(g["idx"], ref_idx, ref_logits, 2)
+        assert not bad
+        near_total += len(near)
+        exact_total += exact
+        # the fp64 oracle may order the twin rows differently from the fp32 one: that is what a near-tie is
+        idx64, _ = oracle64.route(oracle64.gate_logits(x, wl.gate[0]), 2)
+        for t in near:
+            assert {1, 5} & set(g["idx"][t].tolist())
+    print("near-tie test: exact", exact_total, "near-ties", near_total)
+    L.close()

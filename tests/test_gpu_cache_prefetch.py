@@ -188,3 +188,54 @@ def test_stress_small_budgets_random_order_async():
         st = L.ctx.expert_cache_stats()
         assert st["evictions"] > 0 and st["prefetch_issued"] > 0
         L.close()
+
+
+def test_contexts_release_their_memory_and_threads():
+    # create / use / destroy repeatedly: HBM returns to the pool, worker threads are joined
+    import threading
+    import torch
+    from paper_2510_10302_amd import workload as W
+    wl = W.Workload(d=512, f=1024, E=8, k=2, shared=1, dtype="bf16", layers=4, seed=51)
+    threads0 = threading.active_count()
+    x = torch.from_numpy(si.hidden(51, 8, 512)).cuda()
+    out = torch.empty((8, 512), device="cuda")
+
+    def cycle(n):
+        for rep in range(n):
+            L = W.Loaded(wl, W.make_config(wl, max_tokens=8, slots=3, cutoff_layer=3), warm=False)
+            for l in range(4):
+                L.ctx.predict_prefetch_async(l, x[:2])      # starts the worker thread
+            for l in range(4):
+                L.ctx.moe_verify_layer(l, x, out)
+            L.close()
+        torch.cuda.synchronize()
+        return torch.cuda.mem_get_info()[0]
+
+    free_warm = cycle(2)          # first uses load code objects and grow the runtime's own pools
+    free_end = cycle(8)
+    print("free HBM after 2 cycles %.1f MiB, after 10 cycles %.1f MiB" % (free_warm / 2 ** 20, free_end / 2 ** 20))
+    assert free_warm - free_end < 8 * 2 ** 20, "leaked %.1f MiB over 8 create/destroy cycles" % ((free_warm - free_end) / 2 ** 20)
+    assert threading.active_count() == threads0
+
+
+def test_unregistered_expert_is_reported_not_dereferenced():
+    import torch
+    import paper_2510_10302_amd as sp
+    from paper_2510_10302_amd import workload as W
+    wl = W.Workload(d=128, f=128, E=4, k=2, shared=0, dtype="bf16", layers=1, seed=52)
+    cfg = W.make_config(wl, max_tokens=8, slots=2)
+    ctx = sp.Context(cfg)
+    x = torch.from_numpy(si.hidden(52, 8, 128)).cuda()
+    out = torch.empty((8, 128), device="cuda")
+    with pytest.raises(sp.SpmoeError) as e:
+        ctx.moe_verify_layer(0, x, out)                   # gate not set
+    assert e.value.status_name == "SPMOE_ESTATE"
+    g = torch.from_numpy(wl.gate[0].view(np.int16)).cuda()
+    ctx.set_gate(0, g)
+    with pytest.raises(sp.SpmoeError) as e:
+        ctx.moe_verify_layer(0, x, out)                   # experts needed but none registered
+    assert e.value.status_name == "SPMOE_ESTATE" and "not registered" in str(e.value)
+    with pytest.raises(sp.SpmoeError) as e:
+        ctx.expert_cache_warm(0, [1])
+    assert e.value.status_name == "SPMOE_ESTATE"
+    ctx.destroy()

@@ -83,8 +83,6 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
     return v;
 }
 
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __builtin_bit_cast(float, bits16 << 16); }
-
 // fp32 -> bf16 bits, round to nearest even (finite inputs)
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     uint32_t u = __builtin_bit_cast(uint32_t, f);

@@ -102,7 +102,8 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 #define GROUP_MAX_A (SPMOE_MAX_TOKENS * SPMOE_MAX_TOPK)   // 256 routed assignments at most
 
 __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n_shared, int32_t* counts,
-                                  int32_t* offsets, int32_t* perm, int* s_idx, int* s_cnt, int* s_scan) {
+                                  int32_t* offsets, int32_t* perm, int* s_idx, int* s_cnt, int* s_scan,
+                                  int32_t* steal = nullptr) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int A = T * k;
     const int E_tot = E + n_shared;
@@ -141,6 +142,7 @@ __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n
         perm[s_scan[e] + rank] = a;
     }
     for (int a = A + tid; a < A + n_shared * T; a += nthr) perm[a] = a;
+    if (steal != nullptr && tid < 2) steal[tid] = 0;   // unit counters of the two expert GEMMs that follow
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict_
                                                         int32_t* __restrict__ idx_out, float* __restrict__ w_out,
                                                         float* __restrict__ logits_out, int do_group, int n_shared,
                                                         int32_t* counts, int32_t* offsets, int32_t* perm,
-                                                        int32_t* ticket) {
+                                                        int32_t* ticket, int32_t* steal) {
     __shared__ float s_logit[SPMOE_MAX_EXPERTS];
     __shared__ int s_idx[GROUP_MAX_A];
     __shared__ int s_cnt[512];
@@ -315,7 +317,7 @@ __global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict_
     }
     __syncthreads();
     if (!s_last) return;
-    group_assignments(idx_out, T, k, E, n_shared, counts, offsets, perm, s_idx, s_cnt, s_scan);
+    group_assignments(idx_out, T, k, E, n_shared, counts, offsets, perm, s_idx, s_cnt, s_scan, steal);
     if (tid == 0) *ticket = 0;
 }
 
@@ -373,6 +375,9 @@ struct GemmParams {
     int32_t waves;        // waves per workgroup = kw * nw
     int32_t kw;           // waves that split the K range of one N sub-tile
     int32_t nw;           // N sub-tiles a workgroup works on side by side (each kw waves)
+    int32_t* steal;       // zeroed counter handing out the last units of the launch one by one, or NULL
+    int32_t dyn_div;      // the last 1/dyn_div of the units goes through that counter
+    int32_t dyn_force;    // 1: use the counter whatever the launch shape (testing)
 };
 
 // largest divisor of ksw that is <= limit (the ring must divide the per-unit step count so that ring
@@ -398,6 +403,7 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
     int* s_grp = reinterpret_cast<int*>(s_mem + 2 * p.waves * NMAT * 256);   // [GEMM_MAX_GROUPS + 1]
     int* s_off = s_grp + GEMM_MAX_GROUPS + 1;             // [SPMOE_MAX_ETOT + 1] copy of offsets
     int* s_perm = s_off + SPMOE_MAX_ETOT + 1;             // [GEMM_MAX_ASSIGN] copy of perm
+    int* s_next = s_perm + GEMM_MAX_ASSIGN;               // [2] unit handed to the workgroup two iterations ahead
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, kg = lane >> 4;
@@ -434,8 +440,37 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
     const int n_groups = s_grp[GEMM_MAX_GROUPS];
     const int upg = p.splits * p.n_tiles;                 // units per group
     const long long U = (long long)n_groups * upg;
-    const int u0 = (int)(U * blockIdx.x / gridDim.x), u1 = (int)(U * (blockIdx.x + 1) / gridDim.x);
-    if (u0 >= u1) return;                                 // uniform over the workgroup
+    // Unit schedule: the first units are cut into gridDim.x equal contiguous ranges; the last 1/dyn_div is handed
+    // out one unit at a time through an atomic counter, so workgroups that stream faster (the XCDs do not all
+    // see the same bandwidth) take more of it and all finish together.  Which workgroup computes a unit does
+    // not change its value.  A stolen unit usually costs a reload of the token tile, so the tail only pays
+    // where finish times spread widely.  Measured, that is the launches with one 8-wave workgroup per CU
+    // (down projection at d = 6144, f = 16384: 8 % faster); with 11- and 16-wave workgroups it changed the
+    // gate/up projection by -1 % ... +1 % and slowed the down projection by 3 %, so those keep the static split.
+    const bool dyn = p.steal != nullptr && (p.dyn_force || (U >= 10ll * gridDim.x && blockDim.x <= 512));
+    const int U_dyn = dyn ? (int)(U / p.dyn_div) : 0;
+    const int U_st = (int)U - U_dyn;
+    const int u0 = (int)((long long)U_st * blockIdx.x / gridDim.x), u1 = (int)((long long)U_st * (blockIdx.x + 1) / gridDim.x);
+    // thread 0 only: takes the next unit off the counter, -1 once they are all handed out
+    auto grab = [&]() -> int {
+        if (U_dyn == 0) return -1;
+        const int v = U_st + atomicAdd(p.steal, 1);
+        return v < (int)U ? v : -1;
+    };
+    // thread 0 only: the unit after u in this workgroup's schedule, -1 at its end
+    auto successor = [&](int u) -> int {
+        if (u < 0) return -1;
+        return (u + 1 < u1) ? u + 1 : grab();
+    };
+    if (tid == 0) {
+        const int first = (u0 < u1) ? u0 : grab();
+        s_next[0] = first;
+        s_next[1] = successor(first);
+    }
+    __syncthreads();
+    int cur = s_next[0], nxt = s_next[1];
+    __syncthreads();                                      // s_next is rewritten inside the loop
+    if (cur < 0) return;                                  // uniform over the workgroup
 
     const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
     const size_t region = (MODE == MODE_DOWN) ? (size_t)2 * p.d * p.f * sizeof(uint16_t) : 0;
@@ -455,7 +490,7 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
     };
 
     int nks = KSW;
-    const bf16x8* wp = unit_ptr(u0, nks);
+    const bf16x8* wp = unit_ptr(cur, nks);
     bf16x8 ring[PF][NMAT];
 #pragma unroll
     for (int j = 0; j < PF; ++j) {
@@ -472,9 +507,12 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
     int a_out = -1;                                       // assignment this thread writes in the epilogue
     int buf = 0;
 
-    for (int u = u0; u < u1; ++u) {
+    for (int it = 0; cur >= 0; ++it) {
+        const int u = cur;
         const int g = u / upg, rem = u - g * upg;
         const int s = rem / p.n_tiles, nt = rem - s * p.n_tiles;
+        int succ = -1;
+        if (tid == 0) succ = successor(nxt);             // its latency hides behind this unit's k-steps
 
         // ---- token tile (B operand) of this wave's K range; reloaded when the group or split changes
         if (g * p.splits + s != cur_gs) {
@@ -514,7 +552,7 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
 
         // ---- stream the unit's KSW k-steps; the ring refills from this unit, then from the next one
         int nks_next = 0;
-        const bf16x8* wp_next = (u + 1 < u1) ? unit_ptr(u + 1, nks_next) : nullptr;
+        const bf16x8* wp_next = (nxt >= 0) ? unit_ptr(nxt, nks_next) : nullptr;
         f32x4 acc[NMAT];
 #pragma unroll
         for (int m = 0; m < NMAT; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -548,8 +586,11 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
         float* red = s_red + buf * (p.waves * NMAT * 256);
 #pragma unroll
         for (int m = 0; m < NMAT; ++m) *reinterpret_cast<f32x4*>(red + ((wave * NMAT + m) * 64 + lane) * 4) = acc[m];
+        if (tid == 0) s_next[it & 1] = succ;
         // LDS writes done, then workgroup barrier; outstanding weight loads keep flying across it
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        cur = nxt;
+        nxt = s_next[it & 1];
         // o -> (sub-tile, token on, feature fi), consecutive threads on consecutive features; small workgroups
         // take several outputs per thread.  The kw partial sums of a sub-tile are added in wave order.
         for (int o = tid; o < 256 * p.nw; o += blockDim.x) {
@@ -675,15 +716,15 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 hipError_t spmoe_launch_gate_topk(hipStream_t stream, int dtype, const float* x, const void* wg, int T, int E, int d,
                                   int k, int renorm, int32_t* idx, float* w, float* logits, int n_shared,
-                                  int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* ticket) {
+                                  int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* ticket, int32_t* steal) {
     const int do_group = counts != nullptr;
     const int threads = (E >= 32) ? 512 : 256;
     if (dtype == SPMOE_BF16)
         hipLaunchKernelGGL(gate_topk_kernel<uint16_t>, dim3(T), dim3(threads), 0, stream, x, static_cast<const uint16_t*>(wg),
-                           T, E, d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket);
+                           T, E, d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket, steal);
     else
         hipLaunchKernelGGL(gate_topk_kernel<float>, dim3(T), dim3(threads), 0, stream, x, static_cast<const float*>(wg), T, E,
-                           d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket);
+                           d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket, steal);
     return hipGetLastError();
 }
 
@@ -782,7 +823,7 @@ static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, con
                                    const GemmParams& p) {
     const int threads = plan.waves() * 64;
     const size_t lds = (size_t)2 * plan.waves() * 2 * 256 * sizeof(float) +
-                       (GEMM_MAX_GROUPS + 1 + SPMOE_MAX_ETOT + 1 + GEMM_MAX_ASSIGN) * sizeof(int);
+                       (GEMM_MAX_GROUPS + 1 + SPMOE_MAX_ETOT + 1 + GEMM_MAX_ASSIGN + 2) * sizeof(int);
     // cache of grid sizes per (instance, waves): [exact ksw index or generic][waves]
     static int grid_cache[2][16][17];
 #define SPMOE_GEMM_CASE(SLOT_, KSW_, EXACT_)                                                                    \
@@ -823,13 +864,23 @@ static GemmParams make_params(const SpmoeShape& s, const SpmoeRouting& r) {
     p.E_tot = s.E + s.n_shared;
     p.ks_total = 0; p.ks_split = 0; p.splits = 1; p.n_tiles = 0;
     p.waves = 4; p.kw = 4; p.nw = 1;
+    p.steal = nullptr;
+    // SPMOE_DYN_DIV (testing and tuning): 0 = static schedule only, v > 0 = last 1/v of the units dynamic where
+    // the kernel's own rule allows it, v < 0 = last 1/|v| dynamic in every launch that has a counter
+    p.dyn_div = 8;
+    p.dyn_force = 0;
+    if (const char* e = getenv("SPMOE_DYN_DIV")) {
+        const int v = atoi(e);
+        if (v >= -64 && v <= 64) { p.dyn_div = v < 0 ? -v : v; p.dyn_force = v < 0; }
+    }
     return p;
 }
 
 hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape& s, const SpmoeExpertList& list,
-                                const SpmoeRouting& r, const float* x, void* h) {
+                                const SpmoeRouting& r, const float* x, void* h, int32_t* steal) {
     if (list.n <= 0) return hipSuccess;
     GemmParams p = make_params(s, r);
+    p.steal = p.dyn_div > 0 ? steal : nullptr;   // SPMOE_DYN_DIV=0: static schedule only
     p.x = x;
     p.h = static_cast<uint16_t*>(h);
     if (dtype == SPMOE_BF16) {
@@ -847,9 +898,10 @@ hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape&
 }
 
 hipError_t spmoe_launch_down(hipStream_t stream, int dtype, const SpmoeShape& s, const SpmoeExpertList& list,
-                             const SpmoeRouting& r, const void* h, float* ypart, int splits) {
+                             const SpmoeRouting& r, const void* h, float* ypart, int splits, int32_t* steal) {
     if (list.n <= 0) return hipSuccess;
     GemmParams p = make_params(s, r);
+    p.steal = p.dyn_div > 0 ? steal : nullptr;   // SPMOE_DYN_DIV=0: static schedule only
     p.h = static_cast<uint16_t*>(const_cast<void*>(h));
     p.ypart = ypart;
     if (dtype == SPMOE_BF16) {

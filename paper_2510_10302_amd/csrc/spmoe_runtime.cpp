@@ -238,7 +238,8 @@ void kernel_mark(spmoe_ctx* c, int i) {
 }
 
 // One launch of the two expert GEMMs for the experts in `list`, timed per kernel when profiling.
-spmoe_status launch_experts(spmoe_ctx* c, int layer, const SpmoeShape& sh, const SpmoeExpertList& list, const float* x) {
+spmoe_status launch_experts(spmoe_ctx* c, int layer, const SpmoeShape& sh, const SpmoeExpertList& list, const float* x,
+                            bool first_after_routing = false) {
     if (list.n <= 0) return SPMOE_OK;
     TimedSpan k2{nullptr, nullptr, 1, 0, list.n}, k3{nullptr, nullptr, 2, 0, list.n};
     size_t busy;
@@ -252,9 +253,12 @@ spmoe_status launch_experts(spmoe_ctx* c, int layer, const SpmoeShape& sh, const
         k3.begin = k2.end;
         HIP_TRY(c, hipEventRecord(k2.begin, c->compute));
     }
-    HIP_TRY(c, spmoe_launch_gate_up(c->compute, c->cfg.weight_dtype, sh, list, c->route, x, c->h));
+    // the routing kernel zeroed the two unit counters: only the first GEMM pair after it may use them
+    int32_t* steal = first_after_routing ? c->route.steal : nullptr;
+    HIP_TRY(c, spmoe_launch_gate_up(c->compute, c->cfg.weight_dtype, sh, list, c->route, x, c->h, steal));
     if (timed) HIP_TRY(c, hipEventRecord(k2.end, c->compute));
-    HIP_TRY(c, spmoe_launch_down(c->compute, c->cfg.weight_dtype, sh, list, c->route, c->h, c->ypart, c->down_splits));
+    HIP_TRY(c, spmoe_launch_down(c->compute, c->cfg.weight_dtype, sh, list, c->route, c->h, c->ypart, c->down_splits,
+                                 steal ? steal + 1 : nullptr));
     if (timed) {
         HIP_TRY(c, hipEventRecord(k3.end, c->compute));
         c->kspans.push_back(k2);
@@ -346,7 +350,7 @@ spmoe_status launch_prediction(spmoe_ctx* c, int layer, const float* dev_draft_x
     if (st != SPMOE_OK) return st;
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_draft_x, c->layers[layer].gate, n,
                                       c->cfg.n_experts, c->cfg.d_model, pk, 0, dev_idx, dev_p, nullptr, 0, nullptr, nullptr,
-                                      nullptr, nullptr));
+                                      nullptr, nullptr, nullptr));
     HIP_TRY(c, hipMemcpyAsync(host_idx, dev_idx, sizeof(int32_t) * n * pk, hipMemcpyDeviceToHost, c->compute));
     HIP_TRY(c, hipMemcpyAsync(host_p, dev_p, sizeof(float) * n * pk, hipMemcpyDeviceToHost, c->compute));
     return span_end(c, c->compute, span);
@@ -540,7 +544,9 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
         if ((e = hipMalloc(&r.offsets, sizeof(int32_t) * (E_tot + 1))) != hipSuccess) return e;
         if ((e = hipMalloc(&r.perm, sizeof(int32_t) * (Tm * k + cfg->n_shared * Tm))) != hipSuccess) return e;
         if ((e = hipMalloc(&r.ticket, sizeof(int32_t))) != hipSuccess) return e;
+        if ((e = hipMalloc(&r.steal, 2 * sizeof(int32_t))) != hipSuccess) return e;
         // the arrival counter must be zero before the first routing kernel: clear it on the compute stream
+        if ((e = hipMemsetAsync(r.steal, 0, 2 * sizeof(int32_t), c->compute)) != hipSuccess) return e;
         if ((e = hipMemsetAsync(r.ticket, 0, sizeof(int32_t), c->compute)) != hipSuccess) return e;
         return hipStreamSynchronize(c->compute);
     };
@@ -594,7 +600,7 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
     }
     auto free_routing = [](SpmoeRouting& r) {
         (void)hipFree(r.idx); (void)hipFree(r.w); (void)hipFree(r.logits); (void)hipFree(r.counts);
-        (void)hipFree(r.offsets); (void)hipFree(r.perm); (void)hipFree(r.ticket);
+        (void)hipFree(r.offsets); (void)hipFree(r.perm); (void)hipFree(r.ticket); (void)hipFree(r.steal);
     };
     free_routing(c->route);
     free_routing(c->pred);
@@ -754,7 +760,7 @@ spmoe_status spmoe_gate_topk(spmoe_ctx* c, int layer, const float* dev_x, int T,
     if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_x, c->layers[layer].gate, T, c->cfg.n_experts,
                                       c->cfg.d_model, k, c->cfg.renorm_topk, dev_idx, dev_w, dev_logits, 0, nullptr,
-                                      nullptr, nullptr, nullptr));
+                                      nullptr, nullptr, nullptr, nullptr));
     return SPMOE_OK;
 }
 
@@ -879,7 +885,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
     if (st != SPMOE_OK) return st;
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, dt, dev_x, L.gate, T, E, c->cfg.d_model, c->cfg.top_k,
                                       c->cfg.renorm_topk, c->route.idx, c->route.w, c->route.logits, c->cfg.n_shared,
-                                      c->route.counts, c->route.offsets, c->route.perm, c->route.ticket));
+                                      c->route.counts, c->route.offsets, c->route.perm, c->route.ticket, c->route.steal));
     st = span_end(c, c->compute, k1span);
     if (st != SPMOE_OK) return st;
     kernel_mark(c, 1);
@@ -896,7 +902,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
             if (!copy_done(sl)) HIP_TRY(c, hipStreamWaitEvent(c->compute, sl.ready, 0));
             add(e, sl.dev);
         }
-        st = launch_experts(c, layer, sh, list, dev_x);
+        st = launch_experts(c, layer, sh, list, dev_x, true);
         if (st != SPMOE_OK) return st;
     } else {
         // offloaded experts: the per-expert token counts decide which experts this batch needs
@@ -929,7 +935,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
         });
         for (int s = 0; s < c->cfg.n_shared; ++s) add(E + s, L.shared_dev[s]);
         for (int e : landed) add(e, L.slots[L.slot_of[e]].dev);
-        st = launch_experts(c, layer, sh, list, dev_x);
+        st = launch_experts(c, layer, sh, list, dev_x, true);
         if (st != SPMOE_OK) return st;
         for (int e : landed) {
             Slot& sl = L.slots[L.slot_of[e]];

@@ -360,3 +360,31 @@ def test_free_running_chain_of_layers(oracle32):
           % (n_layers, err, sorted(flipped)))
     assert len(good) >= T - 1 and err < 1e-2
     L.close()
+
+
+@pytest.mark.parametrize("d,f,E,k,shared,T", [
+    (256, 416, 8, 2, 0, 11),      # ragged contraction, fewer units than workgroups
+    (512, 1408, 64, 6, 2, 16),    # many groups, shared experts
+    (128, 96, 4, 2, 0, 32),       # two token tiles per expert
+    (2048, 4096, 8, 2, 0, 8),     # many units per workgroup
+])
+def test_unit_schedule_does_not_change_results(d, f, E, k, shared, T, oracle32, monkeypatch):
+    # The expert GEMMs hand out the tail of their work units through an atomic counter.  Which workgroup
+    # computes a unit must not change any bit of the output: static split, the last quarter dynamic, and every
+    # unit dynamic give identical results, call after call (the counters are re-zeroed by the routing kernel).
+    wl = _wl(d=d, f=f, E=E, k=k, shared=shared, dtype="bf16", layers=1, seed=11, gate_std=0.05, std=0.05)
+    L = _loaded(wl, T)
+    x = si.hidden(11, T, d)
+    ref = oracle_layer(oracle32, wl, 0, x)
+    outs = {}
+    for mode in ("0", "-4", "-1", "-1", "8"):
+        monkeypatch.setenv("SPMOE_DYN_DIV", mode)
+        g = gpu_layer(L, 0, x)
+        check_layer(g, ref, k, REL_L2_BF16)
+        outs.setdefault(mode, []).append(g["out"])
+    monkeypatch.delenv("SPMOE_DYN_DIV")
+    base = gpu_layer(L, 0, x)["out"]
+    for mode, lst in outs.items():
+        for o in lst:
+            assert np.array_equal(o.view(np.uint32), base.view(np.uint32)), "schedule %s changed the output" % mode
+    L.close()

@@ -8,7 +8,9 @@
  *   (2) the speculative expert prefetch that feeds it: experts predicted from draft-stage hidden
  *       states with the target layer's gate (paper, Alg. 1) are copied from pinned host memory into
  *       a per-layer LRU cache of HBM slots on a dedicated copy stream (paper, Alg. 2 and the
- *       "Cache Implementation" paragraph), up to a cutoff layer L.
+ *       "Cache Implementation" paragraph), up to a cutoff layer L.  Experts a verification pass finds
+ *       missing are copied on a second stream of the same priority, so they share the link with
+ *       prefetches still in flight instead of waiting behind them.
  *
  * Conventions
  *   - Every function returns an spmoe_status (SPMOE_OK == 0) and never aborts or throws; on error
@@ -17,7 +19,7 @@
  *     Arguments named host_*  are ordinary host pointers owned by the caller.
  *     Arguments named pinned_* are page-locked host memory (hipHostMalloc) owned by the caller and
  *     only BORROWED by the library: they must stay allocated until spmoe_destroy().
- *   - The library owns its cache slots, scratch buffers, copy stream and events.
+ *   - The library owns its cache slots, scratch buffers, its two copy streams and events.
  *   - Kernels run on the compute stream passed to spmoe_create() (a hipStream_t, borrowed; NULL is
  *     the default stream).  Hot-path calls are asynchronous with respect to the device, except
  *     where stated (a few integers of routing are needed on the host when experts are offloaded).
@@ -99,14 +101,14 @@ typedef struct {
 /* ---- life cycle -------------------------------------------------------------------------------*/
 
 /* Creates a context: allocates n_layers * cache_slots_per_layer expert slots (plus shared-expert
- * slots) in HBM, scratch for max_tokens tokens, the copy stream and events.  compute_stream is a
+ * slots) in HBM, scratch for max_tokens tokens, the copy streams and events.  compute_stream is a
  * hipStream_t borrowed for the context's lifetime.  Errors: SPMOE_EINVAL, SPMOE_ERANGE, SPMOE_ENOMEM. */
 spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_ctx** out);
 
-/* Waits for both streams, frees everything the library allocated.  NULL is accepted. */
+/* Waits for the compute stream and the copy streams, frees everything the library allocated.  NULL is accepted. */
 spmoe_status spmoe_destroy(spmoe_ctx* ctx);
 
-/* Waits until the compute stream and the copy stream are idle. */
+/* Waits until the prefetch worker, the compute stream and the copy streams are idle. */
 spmoe_status spmoe_sync(spmoe_ctx* ctx);
 
 /* Human-readable description of the last failure on this context ("" if none; never NULL). */
@@ -183,7 +185,7 @@ spmoe_status spmoe_predict_experts(spmoe_ctx* ctx, int layer, const float* dev_d
                                    int32_t* host_ids_out, int32_t* host_n_out);
 
 /* Alg. 1 lines 9-10 + Alg. 2 for one layer's task: the listed experts that are not resident are
- * copied, back to back on the copy stream, into the slots of as many LRU victims; experts that are
+ * copied, back to back on the prefetch copy stream, into the slots of as many LRU victims; experts that are
  * resident are only moved to the tail of the LRU queue.  A list longer than cache_slots_per_layer is
  * cut to that length.  No-op beyond the cutoff layer.  Returns without waiting for the copies. */
 spmoe_status spmoe_prefetch(spmoe_ctx* ctx, int layer, const int32_t* host_experts, int n);

@@ -7,6 +7,7 @@
 #include <condition_variable>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -21,7 +22,8 @@ namespace {
 struct Slot {
     void* dev = nullptr;
     int expert = -1;              // routed expert id held, -1 = empty
-    hipEvent_t ready = nullptr;   // recorded on the copy stream after the slot's last copy
+    hipEvent_t ready = nullptr;   // recorded after the slot's last copy, on the stream that carried it
+    hipStream_t ready_stream = nullptr;   // that stream
     hipEvent_t freed = nullptr;   // recorded on the compute stream after the last kernel that reads the slot
     bool ready_pending = false;   // a copy was issued and not yet known to have finished
     bool freed_valid = false;     // `freed` has been recorded since the slot was last written
@@ -66,7 +68,8 @@ static int g_prof_active = 0;
 struct spmoe_ctx {
     spmoe_config cfg;
     hipStream_t compute = nullptr;
-    hipStream_t copy = nullptr;
+    hipStream_t copy = nullptr;      // prefetch copies (Alg. 2)
+    hipStream_t demand = nullptr;    // copies of experts a verify pass is waiting for: not queued behind prefetches
     size_t blob_bytes = 0;
     std::vector<Layer> layers;
     spmoe_stats stats;
@@ -188,21 +191,27 @@ spmoe_status span_end(spmoe_ctx* c, hipStream_t st, size_t id) {
     return SPMOE_OK;
 }
 
-// Issues the copy of `expert` into slot s on the copy stream (waits for the slot's last reader first).
+// Issues the copy of `expert` into slot s: prefetches on the prefetch stream, copies a verify pass (or a
+// warm-up) waits for on the on-demand stream, so that they share the link with prefetches still in flight
+// instead of queueing behind them.  The copy waits for the slot's last reader and, when the slot's previous
+// copy went over the other stream and may still be running, for that copy.
 spmoe_status issue_copy(spmoe_ctx* c, int layer, int expert, int s, bool prefetch) {
     Layer& L = c->layers[layer];
     Slot& sl = L.slots[s];
+    hipStream_t stream = prefetch ? c->copy : c->demand;
     if (sl.freed_valid) {
-        HIP_TRY(c, hipStreamWaitEvent(c->copy, sl.freed, 0));
+        HIP_TRY(c, hipStreamWaitEvent(stream, sl.freed, 0));
         sl.freed_valid = false;
     }
+    if (sl.ready_pending && sl.ready_stream != stream) HIP_TRY(c, hipStreamWaitEvent(stream, sl.ready, 0));
     size_t span;
-    spmoe_status st = span_begin(c, c->copy, prefetch ? 1 : 2, layer, expert, &span);
+    spmoe_status st = span_begin(c, stream, prefetch ? 1 : 2, layer, expert, &span);
     if (st != SPMOE_OK) return st;
-    HIP_TRY(c, hipMemcpyAsync(sl.dev, L.host_blob[expert], c->blob_bytes, hipMemcpyHostToDevice, c->copy));
-    st = span_end(c, c->copy, span);
+    HIP_TRY(c, hipMemcpyAsync(sl.dev, L.host_blob[expert], c->blob_bytes, hipMemcpyHostToDevice, stream));
+    st = span_end(c, stream, span);
     if (st != SPMOE_OK) return st;
-    HIP_TRY(c, hipEventRecord(sl.ready, c->copy));
+    HIP_TRY(c, hipEventRecord(sl.ready, stream));
+    sl.ready_stream = stream;
     sl.ready_pending = true;
     sl.copy_seq = ++c->copy_seq;
     sl.expert = expert;
@@ -358,6 +367,7 @@ spmoe_status launch_prediction(spmoe_ctx* c, int layer, const float* dev_draft_x
 
 spmoe_status sync_streams(spmoe_ctx* c) {
     HIP_TRY(c, hipStreamSynchronize(c->copy));
+    HIP_TRY(c, hipStreamSynchronize(c->demand));
     HIP_TRY(c, hipStreamSynchronize(c->compute));
     return SPMOE_OK;
 }
@@ -533,6 +543,10 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
     } while (0)
 
     CREATE_TRY(hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking));
+    // SPMOE_ONE_COPY_STREAM=1 (measurement only): on-demand copies queue behind the prefetches on one stream
+    const char* one = getenv("SPMOE_ONE_COPY_STREAM");
+    if (one && one[0] == '1') c->demand = c->copy;
+    else CREATE_TRY(hipStreamCreateWithFlags(&c->demand, hipStreamNonBlocking));
     CREATE_TRY(hipEventCreateWithFlags(&c->host_ready, hipEventDisableTiming));
     const int pk = std::max(cfg->pred_k, 1);
     auto alloc_routing = [&](SpmoeRouting& r, int k) -> hipError_t {
@@ -583,6 +597,7 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
     stop_worker(c);
     (void)hipStreamSynchronize(c->compute);
     if (c->copy) (void)hipStreamSynchronize(c->copy);
+    if (c->demand) (void)hipStreamSynchronize(c->demand);
     free_spans(c);
     free_kspans(c);
     for (auto& e : c->kev) if (e) (void)hipEventDestroy(e);
@@ -610,6 +625,7 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
     if (c->host_pred_idx) (void)hipHostFree(c->host_pred_idx);
     if (c->host_pred_p) (void)hipHostFree(c->host_pred_p);
     if (c->host_ready) (void)hipEventDestroy(c->host_ready);
+    if (c->demand && c->demand != c->copy) (void)hipStreamDestroy(c->demand);
     if (c->copy) (void)hipStreamDestroy(c->copy);
     delete c;
     return SPMOE_OK;
@@ -689,6 +705,7 @@ spmoe_status spmoe_expert_cache_warm(spmoe_ctx* c, int layer, const int32_t* hos
         c->stats.h2d_bytes_ondemand -= (int64_t)c->blob_bytes;
     }
     HIP_TRY(c, hipStreamSynchronize(c->copy));
+    HIP_TRY(c, hipStreamSynchronize(c->demand));
     for (auto& sl : L.slots) sl.ready_pending = false;
     return SPMOE_OK;
 }
@@ -1033,8 +1050,10 @@ spmoe_status spmoe_profile_begin(spmoe_ctx* c, int mode) {
     Guard guard(c);
     if (guard.st != SPMOE_OK) return guard.st;
     free_spans(c);
-    HIP_TRY(c, hipStreamSynchronize(c->copy));
-    HIP_TRY(c, hipStreamSynchronize(c->compute));
+    {
+        spmoe_status st = sync_streams(c);
+        if (st != SPMOE_OK) return st;
+    }
     {
         std::lock_guard<std::mutex> lk(g_prof_mu);
         if (!c->profiling) {

@@ -819,13 +819,9 @@ spmoe_status spmoe_predict_experts(spmoe_ctx* c, int layer, const float* dev_dra
 }
 
 spmoe_status spmoe_predict_prefetch_async(spmoe_ctx* c, int layer, const float* dev_draft_x, int n) {
-    spmoe_status st = check_layer(c, layer);
-    if (st != SPMOE_OK) return st;
-    if (n < 0 || n > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "n=%d exceeds max_tokens=%d", n, c->cfg.max_tokens);
-    if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer || n == 0 || c->cfg.pred_k < 1) return SPMOE_OK;
-    if (!dev_draft_x) return fail(c, SPMOE_EINVAL, "NULL pointer");
-    if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
+    if (!c) return SPMOE_EINVAL;
     LoadTask* t = nullptr;
+    spmoe_status st = SPMOE_OK;
     {
         std::unique_lock<std::mutex> lk(c->q_mu);
         if (c->worker_status != SPMOE_OK) {
@@ -837,7 +833,14 @@ spmoe_status spmoe_predict_prefetch_async(spmoe_ctx* c, int layer, const float* 
         c->q_done.wait(lk, [&] { return c->q_enqueued - c->q_finished < (uint64_t)kLoadQueueSlots; });
     }
     {
-        std::lock_guard<std::mutex> meta(c->meta_mu);      // profiling spans and the error string are shared
+        // the error string, the profiling spans and the configuration are shared with the worker
+        std::lock_guard<std::mutex> meta(c->meta_mu);
+        st = check_layer(c, layer);
+        if (st != SPMOE_OK) return st;
+        if (n < 0 || n > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "n=%d exceeds max_tokens=%d", n, c->cfg.max_tokens);
+        if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer || n == 0 || c->cfg.pred_k < 1) return SPMOE_OK;
+        if (!dev_draft_x) return fail(c, SPMOE_EINVAL, "NULL pointer");
+        if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
         st = start_worker(c);
         if (st != SPMOE_OK) return st;
         t = &c->q_load[c->q_enqueued % kLoadQueueSlots];   // only this thread advances q_enqueued
@@ -1090,8 +1093,12 @@ spmoe_status spmoe_profile_collect(spmoe_ctx* c, spmoe_profile_record* host_out,
         const TimedSpan& s = c->spans[i];
         float b = 0.f, e = 0.f;
         if (s.begin && s.end) {
-            HIP_TRY(c, hipEventElapsedTime(&b, c->prof_origin, s.begin));
-            HIP_TRY(c, hipEventElapsedTime(&e, c->prof_origin, s.end));
+            // a span whose call failed half-way has an end event that was never recorded: reported as 0, 0
+            if (hipEventElapsedTime(&b, c->prof_origin, s.begin) != hipSuccess ||
+                hipEventElapsedTime(&e, c->prof_origin, s.end) != hipSuccess) {
+                (void)hipGetLastError();
+                b = e = 0.f;
+            }
         }
         host_out[i] = spmoe_profile_record{s.kind, s.layer, s.expert, 0, b, e};
     }

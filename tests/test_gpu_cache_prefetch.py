@@ -239,3 +239,47 @@ def test_unregistered_expert_is_reported_not_dereferenced():
         ctx.expert_cache_warm(0, [1])
     assert e.value.status_name == "SPMOE_ESTATE"
     ctx.destroy()
+
+
+def test_resident_layer_can_be_captured_in_a_hip_graph():
+    # With every expert resident a verify-layer call needs nothing on the host: four kernel launches on the
+    # compute stream, no memset, no synchronisation (the routing kernel re-zeroes its own counters).  It can
+    # therefore be captured once and replayed.  Each replay, with eager work and synchronisations in between
+    # and with new inputs written into the captured buffers, must equal the eager result bit for bit.
+    import torch
+    from paper_2510_10302_amd import workload as W
+    wl = W.Workload(d=512, f=1408, E=16, k=2, shared=1, dtype="bf16", layers=2, seed=21, gate_std=0.05, std=0.05)
+    T = 8
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        L = W.Loaded(wl, W.make_config(wl, max_tokens=T), stream=stream)
+        xs = [torch.from_numpy(si.hidden(300 + i, T, wl.d)).cuda() for i in range(4)]
+        x_in = torch.zeros_like(xs[0])
+        mid = torch.zeros_like(xs[0])
+        out = torch.zeros_like(xs[0])
+
+        def two_layers(src, tmp, dst):
+            L.ctx.moe_verify_layer(0, src, tmp)
+            L.ctx.moe_verify_layer(1, tmp, dst)
+
+        eager = []
+        for x in xs:                                   # also the warm-up that sizes the launches
+            o = torch.empty_like(x)
+            two_layers(x, mid, o)
+            eager.append(o.clone())
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            two_layers(x_in, mid, out)
+        for rep in range(3):
+            for i, x in enumerate(xs):
+                x_in.copy_(x)
+                graph.replay()
+                got = out.clone()
+                # eager work of the same context between replays
+                o = torch.empty_like(x)
+                two_layers(xs[(i + 1) % 4], mid, o)
+                stream.synchronize()
+                assert torch.equal(got.view(torch.int32), eager[i].view(torch.int32)), (rep, i)
+                assert torch.equal(o.view(torch.int32), eager[(i + 1) % 4].view(torch.int32)), (rep, i)
+    L.close()

@@ -336,7 +336,8 @@ __global__ __launch_bounds__(256) void permute_kernel(const int32_t* idx, int T,
 // Work unit = (group, K-split, N-tile): a group is one expert of the launch's list together with a
 // tile of <= 16 of its tokens; an N-tile is 16 weight rows.  All units of a launch are numbered
 // group-major and cut into gridDim.x equal contiguous ranges, one per workgroup, so every workgroup
-// streams the same number of weight bytes whatever the routing was.
+// streams the same number of weight bytes whatever the routing was; launches of 8-wave workgroups keep the
+// last eighth of the units out of the ranges and hand them out one by one through an atomic counter.
 //
 // Inside a workgroup the W waves split the K range of a unit (KSW k-steps each, 1 KiB per matrix per
 // k-step).  A wave keeps its slice of the token tile as the MFMA B operand in registers (reloaded only

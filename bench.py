@@ -226,6 +226,8 @@ def main():
     ap.add_argument("--workload", default="c2_mixtral_8x7b")
     ap.add_argument("--batches", type=int, default=20, help="distinct synthetic token batches cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="resident layer only: capture one pass over the batches in a HIP graph and time its replays")
     ap.add_argument("--resident", action="store_true",
                     help="time one layer of the workload's shape with every expert resident (compute-only number)")
     ap.add_argument("--token-corr", type=float, default=0.0, metavar="RHO",
@@ -287,7 +289,9 @@ def main():
     t0 = time.time()
     wl = W.Workload(d=d, f=f, E=E, k=k, shared=n_shared, dtype=spec["dtype"], layers=1, seed=0)
     cfg = W.make_config(wl, max_tokens=T)
-    L = W.Loaded(wl, cfg)
+    stream = torch.cuda.Stream() if args.graph else torch.cuda.current_stream()
+    torch.cuda.set_stream(stream)
+    L = W.Loaded(wl, cfg, stream=stream)
     log("bench: workload %s built in %.1f s (expert blob %.1f MiB)" % (args.workload, time.time() - t0,
                                                                        W.sp.expert_blob_bytes(cfg) / 2 ** 20))
     ctx = L.ctx
@@ -312,9 +316,22 @@ def main():
         step(i)
     ctx.sync()
     torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    if args.graph:
+        # one graph = one pass over the batches; a step is still one verify-layer call
+        args.steps = max(len(xs), args.steps // len(xs) * len(xs))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(len(xs)):
+                step(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        for _ in range(args.steps // len(xs)):
+            graph.replay()
+    else:
+        t_start = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
     ctx.sync()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
@@ -358,7 +375,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "d_model": d, "d_ff": f, "n_experts": E, "top_k": k, "n_shared": n_shared,
                    "verify_tokens": T, "experts_resident": True, "mean_active_experts": float(np.mean(e_act)),
-                   "token_corr": args.token_corr, "sequences": args.sequences},
+                   "token_corr": args.token_corr, "sequences": args.sequences, "hip_graph": bool(args.graph)},
         "kernels_ms": {"route": float(kms[0]), "gate_up": float(kms[1]), "down": float(kms[2]), "combine": float(kms[3])},
         "expert_gemm_gbs": {"gate_up": gu_gbs, "down": dn_gbs, "both": both_gbs},
         "roofline": {"bound": "hbm", "kernel": "expert_gemm_kernel<gate_up>", "achieved": gu_gbs, "peak": HBM_PEAK_GBS,

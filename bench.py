@@ -191,6 +191,10 @@ def run_offload(spec, args):
     n_pre = sum(1 for r in recs if r["kind"] == 1)
     n_ond = sum(1 for r in recs if r["kind"] == 2)
     h2d_gbs = ((n_pre + n_ond) * blob / 1e9) / (max(measure(union(pre + ond)), 1e-9) * 1e-3)
+    # time the compute stream spent, inside verify-layer calls, waiting for a copy to land: for cached experts
+    # whose prefetch was still in flight (kind 7) and for on-demand loads (kinds 8, 9)
+    wait_pre = sum(r["t1"] - r["t0"] for r in recs if r["kind"] == 7)
+    wait_ond = sum(r["t1"] - r["t0"] for r in recs if r["kind"] in (8, 9))
 
     ms_per_step = elapsed * 1e3 / steps
     hits, misses = stats["hits"], stats["misses"]
@@ -209,6 +213,8 @@ def run_offload(spec, args):
                 "prefetch_copy_ms": copy_ms["prefetch"], "ondemand_copy_ms": copy_ms["ondemand"],
                 "prefetch_hidden_frac": hidden["prefetch"] / max(copy_ms["prefetch"], 1e-9),
                 "ondemand_hidden_frac": hidden["ondemand"] / max(copy_ms["ondemand"], 1e-9),
+                "prefetch_wait_ms": wait_pre, "ondemand_wait_ms": wait_ond,
+                "prefetch_unstalled_frac": 1.0 - wait_pre / max(copy_ms["prefetch"], 1e-9),
                 "compute_busy_ms": measure(busy), "profiled_iterations": n_prof},
         "roofline": {"bound": "host-link", "achieved": h2d_gbs, "peak": link_gbs, "unit": "GB/s",
                      "frac": h2d_gbs / link_gbs, "traffic": None},

@@ -90,7 +90,10 @@ typedef struct {
 typedef struct {
     int32_t kind;      /* 0: verify-layer span (first kernel launch to combine, waits included), 1: prefetch copy,
                           2: on-demand copy, 3: predictor kernel + its result copies, 4: one launch of the two expert
-                          GEMMs, 5: routing kernel, 6: combine kernel (3-6: kernels executing) */
+                          GEMMs, 5: routing kernel, 6: combine kernel (3-6: kernels executing), 7 / 8: the compute
+                          stream waiting, inside a verify-layer call, for the copy of a cached expert that a
+                          prefetch (7) or an earlier on-demand load (8) left in flight, 9: for the on-demand copy of
+                          an expert that was missing */
     int32_t layer;
     int32_t expert;    /* copies: expert id; compute spans: number of experts launched */
     int32_t reserved;
@@ -232,7 +235,7 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* ctx, int layer, int expert,
 
 /* Starts recording one record per copy, predictor launch and verify-layer call, in issue order.
  *   mode 0: each record is timed with a pair of HIP events on its stream;
- *   mode 1: as 0, plus every kernel launch inside the verify-layer calls (kinds 4-6, and
+ *   mode 1: as 0, plus every kernel launch and every wait for a copy inside the verify-layer calls (kinds 4-9, and
  *           spmoe_last_layer_kernel_ms), which puts events between the kernels and slows the layer down;
  *   mode 2: no events at all: the records only log kind / layer / expert in issue order (times are 0),
  *           e.g. to label the copies of an external trace.

@@ -28,6 +28,7 @@ struct Slot {
     bool ready_pending = false;   // a copy was issued and not yet known to have finished
     bool freed_valid = false;     // `freed` has been recorded since the slot was last written
     bool unused_prefetch = false; // filled by spmoe_prefetch and not yet used by a verify pass
+    bool by_prefetch = false;     // the slot's last copy was a prefetch
     uint64_t copy_seq = 0;        // issue order of the slot's last copy
 };
 
@@ -216,6 +217,7 @@ spmoe_status issue_copy(spmoe_ctx* c, int layer, int expert, int s, bool prefetc
     sl.copy_seq = ++c->copy_seq;
     sl.expert = expert;
     sl.unused_prefetch = prefetch;
+    sl.by_prefetch = prefetch;
     L.slot_of[expert] = s;
     L.lru.push_back(expert);
     if (prefetch) {
@@ -962,9 +964,14 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
             HIP_TRY(c, hipEventRecord(sl.freed, c->compute));
             sl.freed_valid = true;
         }
-        auto run_one = [&](int e) -> spmoe_status {
+        auto run_one = [&](int e, int wait_kind) -> spmoe_status {
             Slot& sl = L.slots[L.slot_of[e]];
+            size_t wspan;
+            spmoe_status s1 = span_begin(c, c->compute, wait_kind, layer, e, &wspan);
+            if (s1 != SPMOE_OK) return s1;
             HIP_TRY(c, hipStreamWaitEvent(c->compute, sl.ready, 0));
+            s1 = span_end(c, c->compute, wspan);
+            if (s1 != SPMOE_OK) return s1;
             list.n = 0;
             add(e, sl.dev);
             spmoe_status s2 = launch_experts(c, layer, sh, list, dev_x);
@@ -974,7 +981,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
             return SPMOE_OK;
         };
         for (int e : inflight) {
-            st = run_one(e);
+            st = run_one(e, L.slots[L.slot_of[e]].by_prefetch ? 7 : 8);
             if (st != SPMOE_OK) return st;
         }
         // missing experts: loaded on demand into the LRU head's slot, computed as each copy lands
@@ -982,7 +989,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
             const int s = take_slot(c, L);
             st = issue_copy(c, layer, e, s, false);
             if (st != SPMOE_OK) return st;
-            st = run_one(e);
+            st = run_one(e, 9);
             if (st != SPMOE_OK) return st;
         }
     }

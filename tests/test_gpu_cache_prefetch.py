@@ -113,6 +113,12 @@ def test_profile_records_cover_copies_and_layers():
     kinds = [r["kind"] for r in recs]
     assert kinds.count(1) == 2 and kinds.count(0) == 1 and kinds.count(2) >= 1
     assert all(r["t1"] >= r["t0"] >= 0 for r in recs)
+    # every wait of the compute stream for a copy is recorded: one per on-demand load (kind 9); prefetched experts
+    # the batch uses are either already there or waited for (kind 7), never loaded twice
+    assert kinds.count(9) == kinds.count(2)
+    waited = {r["expert"] for r in recs if r["kind"] == 7}
+    assert waited <= {1, 2} and not (waited & {r["expert"] for r in recs if r["kind"] == 2})
+    assert kinds.count(8) == 0
     assert len(ms) == 4 and all(m >= 0 for m in ms) and ms[1] > 0 and ms[2] > 0
     L.close()
 

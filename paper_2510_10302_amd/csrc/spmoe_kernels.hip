@@ -742,7 +742,7 @@ struct GemmPlan {
     int waves() const { return kw * nw; }
 };
 
-static const int kExactKsw[] = {32, 28, 24, 16, 14, 12, 11, 8, 4};
+static const int kExactKsw[] = {32, 28, 24, 16, 14, 12, 11, 10, 8, 4};
 
 static bool is_exact_ksw(int ksw) {
     for (int v : kExactKsw)
@@ -764,7 +764,7 @@ static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char*
             return GemmPlan{s, kw, ksw, nw, true};
     }
     // preference (measured, the differences are small): as few K-splits as possible, one N sub-tile, 9..16 waves
-    static const int kKswPreference[] = {12, 8, 11, 14, 16, 4, 24, 28, 32};
+    static const int kKswPreference[] = {12, 8, 11, 14, 16, 4, 10, 24, 28, 32};
     for (int splits = 1; splits <= max_splits; splits *= 2) {
         if (ks_total % splits) break;
         const int per = ks_total / splits;
@@ -844,6 +844,7 @@ static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, con
             case 11: SPMOE_GEMM_CASE(6, 11, true) break;
             case 8: SPMOE_GEMM_CASE(7, 8, true) break;
             case 4: SPMOE_GEMM_CASE(8, 4, true) break;
+            case 10: SPMOE_GEMM_CASE(10, 10, true) break;
             default: return hipErrorInvalidValue;
         }
     } else {

@@ -71,6 +71,7 @@ struct spmoe_ctx {
     hipStream_t compute = nullptr;
     hipStream_t copy = nullptr;      // prefetch copies (Alg. 2)
     hipStream_t demand = nullptr;    // copies of experts a verify pass is waiting for: not queued behind prefetches
+    int io_chunks = 1;               // copies per expert: 1 = the whole blob at once (batched I/O)
     size_t blob_bytes = 0;
     std::vector<Layer> layers;
     spmoe_stats stats;
@@ -208,7 +209,14 @@ spmoe_status issue_copy(spmoe_ctx* c, int layer, int expert, int s, bool prefetc
     size_t span;
     spmoe_status st = span_begin(c, stream, prefetch ? 1 : 2, layer, expert, &span);
     if (st != SPMOE_OK) return st;
-    HIP_TRY(c, hipMemcpyAsync(sl.dev, L.host_blob[expert], c->blob_bytes, hipMemcpyHostToDevice, stream));
+    // An expert is one contiguous blob, so its three matrices move in one copy (the paper's batched I/O);
+    // io_chunks > 1 splits it into that many copies to measure what the batching is worth.
+    const size_t chunk = ((c->blob_bytes + c->io_chunks - 1) / c->io_chunks + 255) & ~(size_t)255;
+    for (size_t off = 0; off < c->blob_bytes; off += chunk) {
+        const size_t nbytes = std::min(chunk, c->blob_bytes - off);
+        HIP_TRY(c, hipMemcpyAsync(static_cast<char*>(sl.dev) + off, static_cast<const char*>(L.host_blob[expert]) + off,
+                                  nbytes, hipMemcpyHostToDevice, stream));
+    }
     st = span_end(c, stream, span);
     if (st != SPMOE_OK) return st;
     HIP_TRY(c, hipEventRecord(sl.ready, stream));
@@ -549,6 +557,11 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
     const char* one = getenv("SPMOE_ONE_COPY_STREAM");
     if (one && one[0] == '1') c->demand = c->copy;
     else CREATE_TRY(hipStreamCreateWithFlags(&c->demand, hipStreamNonBlocking));
+    // SPMOE_IO_CHUNKS=n (measurement only): every expert is copied as n pieces instead of one
+    if (const char* ch = getenv("SPMOE_IO_CHUNKS")) {
+        const int v = atoi(ch);
+        if (v >= 1 && v <= 4096) c->io_chunks = v;
+    }
     CREATE_TRY(hipEventCreateWithFlags(&c->host_ready, hipEventDisableTiming));
     const int pk = std::max(cfg->pred_k, 1);
     auto alloc_routing = [&](SpmoeRouting& r, int k) -> hipError_t {

@@ -9,8 +9,8 @@
  *       states with the target layer's gate (paper, Alg. 1) are copied from pinned host memory into
  *       a per-layer LRU cache of HBM slots on a dedicated copy stream (paper, Alg. 2 and the
  *       "Cache Implementation" paragraph), up to a cutoff layer L.  Experts a verification pass finds
- *       missing are copied on a second stream of the same priority, so they share the link with
- *       prefetches still in flight instead of waiting behind them.
+ *       missing are copied on two further streams of the same priority, used alternately, so they share
+ *       the link with prefetches still in flight instead of waiting behind them.
  *
  * Conventions
  *   - Every function returns an spmoe_status (SPMOE_OK == 0) and never aborts or throws; on error
@@ -19,7 +19,7 @@
  *     Arguments named host_*  are ordinary host pointers owned by the caller.
  *     Arguments named pinned_* are page-locked host memory (hipHostMalloc) owned by the caller and
  *     only BORROWED by the library: they must stay allocated until spmoe_destroy().
- *   - The library owns its cache slots, scratch buffers, its two copy streams and events.
+ *   - The library owns its cache slots, scratch buffers, its three copy streams and events.
  *   - Kernels run on the compute stream passed to spmoe_create() (a hipStream_t, borrowed; NULL is
  *     the default stream).  Hot-path calls are asynchronous with respect to the device, except
  *     where stated (a few integers of routing are needed on the host when experts are offloaded).

@@ -69,8 +69,14 @@ static int g_prof_active = 0;
 struct spmoe_ctx {
     spmoe_config cfg;
     hipStream_t compute = nullptr;
-    hipStream_t copy = nullptr;      // prefetch copies (Alg. 2)
-    hipStream_t demand = nullptr;    // copies of experts a verify pass is waiting for: not queued behind prefetches
+    // Copy streams, all at default priority.  Prefetch copies (Alg. 2) and the copies a verify pass is waiting
+    // for use different streams, so an on-demand load is not queued behind prefetches; on-demand copies alternate
+    // between two streams, which hides the idle time the link otherwise shows between two dependent copies.
+    // With the caller's compute stream that makes four streams, one per hardware queue of a process (HIP's
+    // default); a fifth stream shares a queue with another one and was measured to serialise behind it.
+    hipStream_t copy[2] = {nullptr, nullptr};
+    hipStream_t demand[2] = {nullptr, nullptr};
+    unsigned copy_rr = 0, demand_rr = 0;
     int io_chunks = 1;               // copies per expert: 1 = the whole blob at once (batched I/O)
     size_t blob_bytes = 0;
     std::vector<Layer> layers;
@@ -200,7 +206,7 @@ spmoe_status span_end(spmoe_ctx* c, hipStream_t st, size_t id) {
 spmoe_status issue_copy(spmoe_ctx* c, int layer, int expert, int s, bool prefetch) {
     Layer& L = c->layers[layer];
     Slot& sl = L.slots[s];
-    hipStream_t stream = prefetch ? c->copy : c->demand;
+    hipStream_t stream = prefetch ? c->copy[c->copy_rr++ & 1] : c->demand[c->demand_rr++ & 1];
     if (sl.freed_valid) {
         HIP_TRY(c, hipStreamWaitEvent(stream, sl.freed, 0));
         sl.freed_valid = false;
@@ -376,8 +382,7 @@ spmoe_status launch_prediction(spmoe_ctx* c, int layer, const float* dev_draft_x
 }
 
 spmoe_status sync_streams(spmoe_ctx* c) {
-    HIP_TRY(c, hipStreamSynchronize(c->copy));
-    HIP_TRY(c, hipStreamSynchronize(c->demand));
+    for (hipStream_t s : {c->copy[0], c->copy[1], c->demand[0], c->demand[1]}) HIP_TRY(c, hipStreamSynchronize(s));
     HIP_TRY(c, hipStreamSynchronize(c->compute));
     return SPMOE_OK;
 }
@@ -552,11 +557,19 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
         }                                                                            \
     } while (0)
 
-    CREATE_TRY(hipStreamCreateWithFlags(&c->copy, hipStreamNonBlocking));
-    // SPMOE_ONE_COPY_STREAM=1 (measurement only): on-demand copies queue behind the prefetches on one stream
-    const char* one = getenv("SPMOE_ONE_COPY_STREAM");
-    if (one && one[0] == '1') c->demand = c->copy;
-    else CREATE_TRY(hipStreamCreateWithFlags(&c->demand, hipStreamNonBlocking));
+    // SPMOE_COPY_STREAMS (measurement only): 1 = a single stream for all copies (on-demand loads queue behind
+    // prefetches), 2 = one stream per kind, 3 = one prefetch stream and two on-demand streams, 4 = two per kind
+    int n_streams = 3;
+    if (const char* e = getenv("SPMOE_COPY_STREAMS")) {
+        if (e[0] >= '1' && e[0] <= '4') n_streams = e[0] - '0';
+    }
+    CREATE_TRY(hipStreamCreateWithFlags(&c->copy[0], hipStreamNonBlocking));
+    if (n_streams == 4) CREATE_TRY(hipStreamCreateWithFlags(&c->copy[1], hipStreamNonBlocking));
+    else c->copy[1] = c->copy[0];
+    if (n_streams == 1) c->demand[0] = c->copy[0];
+    else CREATE_TRY(hipStreamCreateWithFlags(&c->demand[0], hipStreamNonBlocking));
+    if (n_streams >= 3) CREATE_TRY(hipStreamCreateWithFlags(&c->demand[1], hipStreamNonBlocking));
+    else c->demand[1] = c->demand[0];
     // SPMOE_IO_CHUNKS=n (measurement only): every expert is copied as n pieces instead of one
     if (const char* ch = getenv("SPMOE_IO_CHUNKS")) {
         const int v = atoi(ch);
@@ -611,8 +624,8 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
     if (!c) return SPMOE_OK;
     stop_worker(c);
     (void)hipStreamSynchronize(c->compute);
-    if (c->copy) (void)hipStreamSynchronize(c->copy);
-    if (c->demand) (void)hipStreamSynchronize(c->demand);
+    for (hipStream_t s : {c->copy[0], c->copy[1], c->demand[0], c->demand[1]})
+        if (s) (void)hipStreamSynchronize(s);
     free_spans(c);
     free_kspans(c);
     for (auto& e : c->kev) if (e) (void)hipEventDestroy(e);
@@ -640,8 +653,14 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
     if (c->host_pred_idx) (void)hipHostFree(c->host_pred_idx);
     if (c->host_pred_p) (void)hipHostFree(c->host_pred_p);
     if (c->host_ready) (void)hipEventDestroy(c->host_ready);
-    if (c->demand && c->demand != c->copy) (void)hipStreamDestroy(c->demand);
-    if (c->copy) (void)hipStreamDestroy(c->copy);
+    {
+        hipStream_t all[4] = {c->copy[0], c->copy[1], c->demand[0], c->demand[1]};
+        for (int i = 0; i < 4; ++i) {
+            bool seen = !all[i];
+            for (int j = 0; j < i; ++j) seen = seen || all[j] == all[i];
+            if (!seen) (void)hipStreamDestroy(all[i]);
+        }
+    }
     delete c;
     return SPMOE_OK;
 }
@@ -719,8 +738,8 @@ spmoe_status spmoe_expert_cache_warm(spmoe_ctx* c, int layer, const int32_t* hos
         c->stats.ondemand_loads -= 1;
         c->stats.h2d_bytes_ondemand -= (int64_t)c->blob_bytes;
     }
-    HIP_TRY(c, hipStreamSynchronize(c->copy));
-    HIP_TRY(c, hipStreamSynchronize(c->demand));
+    st = sync_streams(c);
+    if (st != SPMOE_OK) return st;
     for (auto& sl : L.slots) sl.ready_pending = false;
     return SPMOE_OK;
 }
@@ -1051,11 +1070,11 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* c, int layer, int expert, i
     float ms = 0.f;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) res = SPMOE_EHIP;
     if (res == SPMOE_OK) {
-        bool ok = hipMemcpyAsync(tmp, src, c->blob_bytes, hipMemcpyHostToDevice, c->copy) == hipSuccess;   // warm-up
-        ok = ok && hipEventRecord(a, c->copy) == hipSuccess;
+        bool ok = hipMemcpyAsync(tmp, src, c->blob_bytes, hipMemcpyHostToDevice, c->copy[0]) == hipSuccess;   // warm-up
+        ok = ok && hipEventRecord(a, c->copy[0]) == hipSuccess;
         for (int i = 0; ok && i < repeats; ++i)
-            ok = hipMemcpyAsync(tmp, src, c->blob_bytes, hipMemcpyHostToDevice, c->copy) == hipSuccess;
-        ok = ok && hipEventRecord(b, c->copy) == hipSuccess && hipEventSynchronize(b) == hipSuccess &&
+            ok = hipMemcpyAsync(tmp, src, c->blob_bytes, hipMemcpyHostToDevice, c->copy[0]) == hipSuccess;
+        ok = ok && hipEventRecord(b, c->copy[0]) == hipSuccess && hipEventSynchronize(b) == hipSuccess &&
              hipEventElapsedTime(&ms, a, b) == hipSuccess;
         if (!ok) res = fail(c, SPMOE_EHIP, "timed copy failed: %s", hipGetErrorString(hipGetLastError()));
     }

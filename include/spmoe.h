@@ -231,6 +231,17 @@ spmoe_status spmoe_suggest_cutoff(int n_layers, int n_layers_draft, int k, doubl
  * time in ms.  Synchronous; does not touch the cache. */
 spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* ctx, int layer, int expert, int repeats, float* host_ms_out);
 
+/* ---- introspection ----------------------------------------------------------------------------*/
+
+/* How the library tiles the two expert GEMMs of a bf16 configuration (the grouped SwiGLU FFN of Eq. 1) over a
+ * workgroup: projection 0 = gate/up (contraction over d_model), 1 = down (contraction over d_ff).
+ * host_plan_out[0] = K-splits across workgroups, [1] = waves that split the K range of one N sub-tile,
+ * [2] = k-steps (of 32 elements) per wave, [3] = N sub-tiles side by side in a workgroup, [4] = 1 if
+ * [0] * [1] * [2] covers the contraction exactly, 0 for the generic instance (zero operands past the end),
+ * [5] = dynamic LDS bytes of the launch.  Pure host arithmetic; SPMOE_EINVAL for a configuration
+ * spmoe_create would refuse or for fp32 weights (which do not use these kernels). */
+spmoe_status spmoe_gemm_plan(const spmoe_config* cfg, int projection, int32_t host_plan_out[6]);
+
 /* ---- measurement ------------------------------------------------------------------------------*/
 
 /* Starts recording one record per copy, predictor launch and verify-layer call, in issue order.

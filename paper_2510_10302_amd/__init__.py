@@ -6,6 +6,6 @@ There is no CPU fallback: importing :mod:`paper_2510_10302_amd.binding` raises i
 not been built (``python -m paper_2510_10302_amd.build`` or ``__graft_entry__.build()``).
 """
 from .binding import (  # noqa: F401
-    SpmoeError, Config, Context, Stats, ProfileRecord, expert_blob_bytes, pack_expert, lib_path, load_library, suggest_cutoff,
+    SpmoeError, Config, Context, Stats, ProfileRecord, expert_blob_bytes, pack_expert, lib_path, load_library, suggest_cutoff, gemm_plan,
     F32, BF16, DECLARED_SYMBOLS,
 )

@@ -23,6 +23,7 @@ DECLARED_SYMBOLS = [
     "spmoe_token_permutation", "spmoe_predict_experts", "spmoe_prefetch", "spmoe_moe_verify_layer",
     "spmoe_profile_begin", "spmoe_profile_collect", "spmoe_last_layer_kernel_ms",
     "spmoe_suggest_cutoff", "spmoe_measure_expert_load_ms", "spmoe_predict_prefetch_async", "spmoe_prefetch_drain",
+    "spmoe_gemm_plan",
 ]
 
 
@@ -104,6 +105,7 @@ def load_library():
         "spmoe_measure_expert_load_ms": (i32, [vp, i32, i32, i32, vp]),
         "spmoe_predict_prefetch_async": (i32, [vp, i32, vp, i32]),
         "spmoe_prefetch_drain": (i32, [vp]),
+        "spmoe_gemm_plan": (i32, [cp, i32, vp]),
     }
     assert sorted(sig) == sorted(DECLARED_SYMBOLS)
     for name, (res, args) in sig.items():
@@ -148,6 +150,15 @@ def suggest_cutoff(n_layers, n_layers_draft, k, t_comp, t_io, m_peak, m_expert, 
     if st != 0:
         raise SpmoeError(st, "spmoe_suggest_cutoff")
     return out.value
+
+
+def gemm_plan(cfg, projection):
+    """Tiling of the gate/up (0) or down (1) expert GEMM: dict(splits, k_waves, k_steps, n_sub, exact, lds_bytes)."""
+    out = (ctypes.c_int32 * 6)()
+    st = load_library().spmoe_gemm_plan(ctypes.byref(cfg), projection, ctypes.addressof(out))
+    if st != 0:
+        raise SpmoeError(st, "spmoe_gemm_plan")
+    return dict(splits=out[0], k_waves=out[1], k_steps=out[2], n_sub=out[3], exact=bool(out[4]), lds_bytes=out[5])
 
 
 def _host_ptr(buf):

@@ -57,5 +57,7 @@ hipError_t spmoe_launch_combine(hipStream_t stream, const SpmoeShape& s, const S
                                 int splits, float* out);
 // Number of K-splits (partial-sum planes of ypart) the down projection uses for this shape.
 int spmoe_down_splits(int dtype, int d, int f);
+// plan of the bf16 expert GEMM of `projection` (0 gate/up, 1 down): splits, kw, ksw, nw, exact, LDS bytes
+void spmoe_describe_plan(int projection, int d, int f, int32_t out[6]);
 
 #endif

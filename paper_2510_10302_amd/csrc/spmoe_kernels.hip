@@ -806,6 +806,17 @@ int spmoe_down_splits(int dtype, int d, int f) {
     return plan_down(d, f).splits;
 }
 
+static size_t gemm_lds_bytes(int waves) {
+    return (size_t)2 * waves * 2 * 256 * sizeof(float) +
+           (GEMM_MAX_GROUPS + 1 + SPMOE_MAX_ETOT + 1 + GEMM_MAX_ASSIGN + 2) * sizeof(int);
+}
+
+void spmoe_describe_plan(int projection, int d, int f, int32_t out[6]) {
+    const GemmPlan p = projection == 0 ? plan_gate_up(d, f) : plan_down(d, f);
+    out[0] = p.splits; out[1] = p.kw; out[2] = p.ksw; out[3] = p.nw; out[4] = p.exact ? 1 : 0;
+    out[5] = (int32_t)gemm_lds_bytes(p.waves());
+}
+
 // Persistent grid size: as many workgroups as fit on the chip at once for this instance.
 template <typename Kernel>
 static int resident_blocks(Kernel kernel, int threads, size_t lds) {
@@ -823,8 +834,7 @@ template <int MODE>
 static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, const SpmoeExpertList& list,
                                    const GemmParams& p) {
     const int threads = plan.waves() * 64;
-    const size_t lds = (size_t)2 * plan.waves() * 2 * 256 * sizeof(float) +
-                       (GEMM_MAX_GROUPS + 1 + SPMOE_MAX_ETOT + 1 + GEMM_MAX_ASSIGN + 2) * sizeof(int);
+    const size_t lds = gemm_lds_bytes(plan.waves());
     // cache of grid sizes per (instance, waves): [exact ksw index or generic][waves]
     static int grid_cache[2][16][17];
 #define SPMOE_GEMM_CASE(SLOT_, KSW_, EXACT_)                                                                    \

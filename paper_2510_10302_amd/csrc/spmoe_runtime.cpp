@@ -1085,6 +1085,16 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* c, int layer, int expert, i
     return res;
 }
 
+// ---- introspection ----------------------------------------------------------------------------------
+
+spmoe_status spmoe_gemm_plan(const spmoe_config* cfg, int projection, int32_t host_plan_out[6]) {
+    const char* why;
+    if (!config_ok(cfg, &why) || !host_plan_out || (projection != 0 && projection != 1)) return SPMOE_EINVAL;
+    if (cfg->weight_dtype != SPMOE_BF16) return SPMOE_EINVAL;
+    spmoe_describe_plan(projection, cfg->d_model, cfg->d_ff, host_plan_out);
+    return SPMOE_OK;
+}
+
 // ---- measurement ------------------------------------------------------------------------------------
 
 spmoe_status spmoe_profile_begin(spmoe_ctx* c, int mode) {

@@ -127,3 +127,38 @@ def test_header_is_plain_c_and_cpp(tmp_path):
                            "-o", str(tmp_path / "abi_c.o")])
     subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-c", str(cpp_file),
                            "-o", str(tmp_path / "abi_cpp.o")])
+
+
+def test_gemm_plans_fit_what_the_kernels_assume(sp):
+    # Host logic that sizes every bf16 expert-GEMM launch: for every shape the library accepts, the plan must
+    # cover the contraction, keep the workgroup within the kernels' launch bounds (16 waves; 8 waves when a
+    # wave holds more than 14 k-steps of the token tile in registers), divide the N tiles evenly and fit the
+    # LDS of a CU.  A plan outside these limits would launch a kernel whose indexing does not match its grid.
+    exact_steps = {4, 8, 10, 11, 12, 14, 16, 24, 28, 32}
+    shapes = [(d, f) for d in range(32, 8193, 32) for f in (32, 64, 96, 1408, 4096, 6400, 14336, 16384)]
+    shapes += [(d, f) for d in (32, 512, 2048, 4096, 6144, 8192) for f in range(32, 32769, 32)]
+    for d, f in shapes:
+        cfg = sp.Config(d_model=d, d_ff=f, n_experts=8, top_k=2, weight_dtype=sp.BF16)
+        for proj, (k_len, n_units) in enumerate([(d // 32, f // 16), (f // 32, d // 32)]):
+            p = sp.gemm_plan(cfg, proj)
+            waves = p["k_waves"] * p["n_sub"]
+            assert 1 <= waves <= 16 and (p["k_steps"] <= 14 or waves <= 8), (d, f, proj, p)
+            assert n_units % p["n_sub"] == 0, (d, f, proj, p)
+            assert p["lds_bytes"] <= 160 * 1024 // 2, (d, f, proj, p)     # two workgroups per CU still fit its 160 KB
+            if proj == 0:
+                assert p["splits"] == 1, (d, f, p)         # SiLU needs the whole contraction in one workgroup
+            if p["exact"]:
+                assert p["k_steps"] in exact_steps, (d, f, proj, p)
+                assert p["splits"] * p["k_waves"] * p["k_steps"] == k_len, (d, f, proj, p)
+            else:
+                per = -(-k_len // p["splits"])
+                assert p["k_steps"] == 32 and p["k_waves"] <= 8 and p["k_waves"] * 32 >= per, (d, f, proj, p)
+    # the benchmark shapes use the plans the measurements were made with
+    c2 = sp.Config(d_model=4096, d_ff=14336, n_experts=8, top_k=2, weight_dtype=sp.BF16)
+    assert (sp.gemm_plan(c2, 0)["k_waves"], sp.gemm_plan(c2, 0)["k_steps"]) == (16, 8)
+    p = sp.gemm_plan(c2, 1)
+    assert (p["splits"], p["k_waves"], p["k_steps"]) == (2, 16, 14)
+    with pytest.raises(sp.SpmoeError):
+        sp.gemm_plan(sp.Config(d_model=512, d_ff=1024, n_experts=8, top_k=2, weight_dtype=sp.F32), 0)
+    with pytest.raises(sp.SpmoeError):
+        sp.gemm_plan(c2, 2)

@@ -19,6 +19,8 @@
  *     Arguments named host_*  are ordinary host pointers owned by the caller.
  *     Arguments named pinned_* are page-locked host memory (hipHostMalloc) owned by the caller and
  *     only BORROWED by the library: they must stay allocated until spmoe_destroy().
+ *     Hidden states, gates and expert blobs are read with 16-byte vector loads: these pointers must be
+ *     16-byte aligned (SPMOE_EINVAL otherwise); rows then stay aligned because d and f are multiples of 32.
  *   - The library owns its cache slots, scratch buffers, its three copy streams and events.
  *   - Kernels run on the compute stream passed to spmoe_create() (a hipStream_t, borrowed; NULL is
  *     the default stream).  Hot-path calls are asynchronous with respect to the device, except

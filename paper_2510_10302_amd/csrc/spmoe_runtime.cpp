@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <condition_variable>
 #include <cstdarg>
+#include <cstdint>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -155,6 +156,9 @@ bool config_ok(const spmoe_config* c, const char** why) {
 }
 
 size_t elem_bytes(int dtype) { return dtype == SPMOE_BF16 ? 2 : 4; }
+
+// The kernels read hidden states, gates and weights with 16-byte vector loads.
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 void lru_touch(Layer& L, int expert) {
     auto it = std::find(L.lru.begin(), L.lru.end(), expert);
@@ -680,6 +684,7 @@ spmoe_status spmoe_set_gate(spmoe_ctx* c, int layer, const void* dev_wg) {
     Guard guard(c);
     if (guard.st != SPMOE_OK) return guard.st;
     if (!dev_wg) return fail(c, SPMOE_EINVAL, "gate pointer is NULL");
+    if (!aligned16(dev_wg)) return fail(c, SPMOE_EINVAL, "gate pointer is not 16-byte aligned");
     c->layers[layer].gate = dev_wg;
     return SPMOE_OK;
 }
@@ -699,6 +704,7 @@ spmoe_status spmoe_expert_cache_register(spmoe_ctx* c, int layer, int expert, co
     if (guard.st != SPMOE_OK) return guard.st;
     if (expert < 0 || expert >= c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "expert %d out of range", expert);
     if (!pinned_blob) return fail(c, SPMOE_EINVAL, "blob pointer is NULL");
+    if (!aligned16(pinned_blob)) return fail(c, SPMOE_EINVAL, "blob pointer is not 16-byte aligned");
     c->layers[layer].host_blob[expert] = pinned_blob;
     return SPMOE_OK;
 }
@@ -808,6 +814,7 @@ spmoe_status spmoe_gate_topk(spmoe_ctx* c, int layer, const float* dev_x, int T,
     if (k < 1 || k > SPMOE_MAX_TOPK || k > c->cfg.n_experts) return fail(c, SPMOE_ERANGE, "k=%d out of range", k);
     if (T == 0) return SPMOE_OK;   // an empty batch is a no-op (its pointers may be NULL)
     if (!dev_x || !dev_idx || !dev_w) return fail(c, SPMOE_EINVAL, "NULL device pointer");
+    if (!aligned16(dev_x)) return fail(c, SPMOE_EINVAL, "dev_x is not 16-byte aligned");
     if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_x, c->layers[layer].gate, T, c->cfg.n_experts,
                                       c->cfg.d_model, k, c->cfg.renorm_topk, dev_idx, dev_w, dev_logits, 0, nullptr,
@@ -834,6 +841,7 @@ spmoe_status spmoe_predict_experts(spmoe_ctx* c, int layer, const float* dev_dra
     Guard guard(c);
     if (guard.st != SPMOE_OK) return guard.st;
     if (!dev_draft_x || !host_ids_out || !host_n_out) return fail(c, SPMOE_EINVAL, "NULL pointer");
+    if (!aligned16(dev_draft_x)) return fail(c, SPMOE_EINVAL, "dev_draft_x is not 16-byte aligned");
     if (n < 0 || n > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "n=%d exceeds max_tokens=%d", n, c->cfg.max_tokens);
     if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer || n == 0 || c->cfg.pred_k < 1) {   // Alg. 1: only l <= L
         *host_n_out = 0;
@@ -874,6 +882,7 @@ spmoe_status spmoe_predict_prefetch_async(spmoe_ctx* c, int layer, const float* 
         if (n < 0 || n > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "n=%d exceeds max_tokens=%d", n, c->cfg.max_tokens);
         if (c->cfg.cutoff_layer < 0 || layer > c->cfg.cutoff_layer || n == 0 || c->cfg.pred_k < 1) return SPMOE_OK;
         if (!dev_draft_x) return fail(c, SPMOE_EINVAL, "NULL pointer");
+        if (!aligned16(dev_draft_x)) return fail(c, SPMOE_EINVAL, "dev_draft_x is not 16-byte aligned");
         if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
         st = start_worker(c);
         if (st != SPMOE_OK) return st;
@@ -920,6 +929,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
     if (T < 0 || T > c->cfg.max_tokens) return fail(c, SPMOE_ERANGE, "T=%d exceeds max_tokens=%d", T, c->cfg.max_tokens);
     if (T == 0) return SPMOE_OK;   // an empty batch is a no-op (its pointers may be NULL)
     if (!dev_x || !dev_out) return fail(c, SPMOE_EINVAL, "NULL device pointer");
+    if (!aligned16(dev_x) || !aligned16(dev_out)) return fail(c, SPMOE_EINVAL, "dev_x / dev_out is not 16-byte aligned");
     Layer& L = c->layers[layer];
     if (!L.gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
     const int E = c->cfg.n_experts, dt = c->cfg.weight_dtype;

@@ -121,6 +121,22 @@ def test_zero_tokens_is_a_noop_and_errors_are_reported():
         L.ctx.gate_topk(0, x5[:4], 5, torch.zeros((4, 5), dtype=torch.int32, device="cuda"),
                         torch.zeros((4, 5), device="cuda"))                         # k > E
     assert e.value.status_name == "SPMOE_ERANGE"
+    # hidden states are read with 16-byte vector loads: a pointer that is off by one float is refused
+    flat = torch.zeros(4 * 64 + 4, device="cuda")
+    shifted = flat[1:1 + 4 * 64].view(4, 64)
+    assert shifted.data_ptr() % 16 == 4 and shifted.is_contiguous()
+    good = torch.zeros((4, 64), device="cuda")
+    with pytest.raises(SpmoeError) as e:
+        L.ctx.moe_verify_layer(0, shifted, good)
+    assert e.value.status_name == "SPMOE_EINVAL"
+    with pytest.raises(SpmoeError) as e:
+        L.ctx.moe_verify_layer(0, good, shifted)
+    assert e.value.status_name == "SPMOE_EINVAL"
+    with pytest.raises(SpmoeError) as e:
+        L.ctx.gate_topk(0, shifted, 2, torch.zeros((4, 2), dtype=torch.int32, device="cuda"), torch.zeros((4, 2), device="cuda"))
+    assert e.value.status_name == "SPMOE_EINVAL"
+    L.ctx.moe_verify_layer(0, good, torch.empty((4, 64), device="cuda"))          # and the context still works
+    L.ctx.sync()
     L.close()
 
 

@@ -171,7 +171,12 @@ def test_measured_load_time_and_suggested_cutoff():
     L.close()
 
 
-def test_stress_small_budgets_random_order_async():
+@pytest.mark.parametrize("copy_streams", ["default", "1", "2", "4"])
+def test_stress_small_budgets_random_order_async(copy_streams, monkeypatch):
+    # copy_streams: how many copy streams the context uses (default: one for prefetches, two alternating for
+    # on-demand loads); a slot may be rewritten over a different stream than the one that filled it last
+    if copy_streams != "default":
+        monkeypatch.setenv("SPMOE_COPY_STREAMS", copy_streams)
     # slot hazards: 1-2 slots per layer, layers visited in random order, worker-thread prefetches racing with
     # verify calls; every output must stay bit-identical to the all-resident run
     import torch

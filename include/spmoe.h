@@ -229,7 +229,7 @@ spmoe_status spmoe_suggest_cutoff(int n_layers, int n_layers_draft, int k, doubl
                                   double m_expert, double m_gpu, int* host_cutoff_out);
 
 /* Profiles the per-expert loading time the policy needs: copies the registered host blob of
- * (layer, expert) into a temporary HBM buffer `repeats` times on the copy stream and returns the mean
+ * (layer, expert) into a temporary HBM buffer `repeats` times on the prefetch copy stream and returns the mean
  * time in ms.  Synchronous; does not touch the cache. */
 spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* ctx, int layer, int expert, int repeats, float* host_ms_out);
 

@@ -182,9 +182,11 @@ spmoe_status spmoe_token_permutation(spmoe_ctx* ctx, const int32_t* dev_idx, int
                                      int32_t* dev_counts, int32_t* dev_offsets, int32_t* dev_perm);
 
 /* Alg. 1 lines 1-6 for n draft-stage hidden states of one layer: if layer <= L, score them with the
- * target layer's gate, take the top pred_k experts per state and drop those already cached.
- * The surviving expert ids land in host_ids_out (capacity n_experts), most-voted first (ties: larger
- * summed probability, then lower index); *host_n_out = their number (0 beyond the cutoff).
+ * target layer's gate, take the top pred_k experts per state, rank them most-voted first (ties: larger
+ * summed probability, then lower index), keep the first cache_slots_per_layer of that ranking (one task
+ * never names more experts than the layer can hold), and drop those already cached, which are moved to
+ * the tail of the LRU queue.  The surviving expert ids land in host_ids_out (capacity n_experts) in
+ * ranking order; *host_n_out = their number (0 beyond the cutoff).
  * Blocks the calling thread until the few bytes of routing have reached the host. */
 spmoe_status spmoe_predict_experts(spmoe_ctx* ctx, int layer, const float* dev_draft_x, int n,
                                    int32_t* host_ids_out, int32_t* host_n_out);
@@ -211,9 +213,10 @@ spmoe_status spmoe_prefetch_drain(spmoe_ctx* ctx);
 /* The MoE block of one layer on T tokens (Eq. 1): out[t] = sum_r w[t][r] * FFN_{idx[t][r]}(x[t])
  * (+ shared experts with weight 1).  Experts already cached are computed first; missing ones are
  * loaded on demand (evicting the LRU head) and computed as their copies land.  When every routed
- * expert of the layer is resident the call is fully asynchronous; otherwise it waits for the
- * per-expert token counts to reach the host before it returns.  The result does not depend on the
- * cache state. */
+ * expert of the layer is resident the call is fully asynchronous: the host never learns the routing,
+ * so that call neither counts hits nor changes the LRU order (nothing can be evicted then anyway).
+ * Otherwise it waits for the per-expert token counts to reach the host before it returns.  The result
+ * does not depend on the cache state. */
 spmoe_status spmoe_moe_verify_layer(spmoe_ctx* ctx, int layer, const float* dev_x, int T, float* dev_out);
 
 /* ---- cutoff-layer policy ("Cutoff layer design") ----------------------------------------------*/

@@ -7,12 +7,15 @@ back).  Readings of points the paper leaves open:
 
 * one queue per layer with a fixed number of slots (the paper reserves "a fixed number of experts
   per layer");
+* a task names at most as many experts as the layer has slots: a ranked prediction (or a raw
+  list) longer than that is cut to the slot count, in the given order, BEFORE the cached ones
+  are dropped (Alg. 1's task is TopK_Index's k experts, and k never exceeds the per-layer
+  budget in the paper);
 * a predicted expert that is already cached is removed from the load list (Alg. 1) *and* touched,
   so the task that predicted it cannot pick it as a victim;
-* a load list longer than the number of slots is cut to the slot count, in the given order;
-* victims are taken from the head of the queue (Alg. 2's "first N entries"); because predicted
-  hits were moved to the tail first and the list is no longer than the slot count, a task never
-  evicts one of its own experts;
+* victims are taken from the head of the queue (Alg. 2's "first N entries"); because the task's
+  cached experts were moved to the tail first and cached + loaded experts of one task are no
+  more than the slot count, a task never evicts one of its own experts;
 * at verification, cached experts are used first, then missing ones are loaded on demand in
   ascending expert order, each evicting the current head (which may be an expert this same batch
   has already used, when the batch needs more experts than there are slots);
@@ -58,13 +61,19 @@ class CacheModel:
 
     # ---- Alg. 1 lines 4-6 + Alg. 2 ---------------------------------------------------------------
     def filter_cached(self, layer, experts):
-        """Alg. 1: drop predicted experts that are already in Q_cache (order kept, duplicates dropped).
-        The cached ones are touched, so the task built from the rest cannot pick them as victims."""
-        seen, out = set(), []
+        """Alg. 1 lines 1 and 4-6 for a ranked prediction: nothing beyond the cutoff layer; duplicates
+        dropped (order kept); the list cut to the slot count; predicted experts already in Q_cache
+        dropped from it.  The cached ones are touched, so the task built from the rest cannot pick
+        them as victims.  Returns the experts left to load."""
+        if self.cutoff < 0 or layer > self.cutoff:
+            return []
+        task = []
         for e in experts:
-            if e in seen:
-                continue
-            seen.add(e)
+            if e not in task:
+                task.append(e)
+        task = task[: self.slots]
+        out = []
+        for e in task:
             if e in self.queue[layer]:
                 self._touch(layer, e)
             else:

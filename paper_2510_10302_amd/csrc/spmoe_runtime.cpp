@@ -319,8 +319,9 @@ spmoe_status check_layer(spmoe_ctx* c, int layer) {
 }
 
 // Host half of Alg. 1 (lines 3-6) on routing that has reached the host: rank the predicted experts
-// (most-voted first, then larger summed probability, then lower index), drop the ones already in
-// Q_cache and move those to the queue tail.  Returns the number of experts left in out_ids.
+// (most-voted first, then larger summed probability, then lower index), keep at most one per cache slot,
+// drop the ones already in Q_cache and move those to the queue tail.  Returns the number of experts left
+// in out_ids.
 spmoe_status rank_and_filter(spmoe_ctx* c, Layer& L, const int32_t* idx, const float* prob, int n, int32_t* out_ids,
                              int* n_out) {
     const int pk = c->cfg.pred_k, E = c->cfg.n_experts;
@@ -340,6 +341,9 @@ spmoe_status rank_and_filter(spmoe_ctx* c, Layer& L, const int32_t* idx, const f
         if (psum[a] != psum[b]) return psum[a] > psum[b];
         return a < b;
     });
+    // A task names at most as many experts as the layer has slots (the least-voted ones are left out), so the
+    // experts it keeps plus the experts it loads always fit, and its loads never evict what it predicted.
+    if ((int)order.size() > c->cfg.cache_slots_per_layer) order.resize(c->cfg.cache_slots_per_layer);
     int m = 0;
     for (int e : order) {
         if (L.slot_of[e] < 0) out_ids[m++] = e;   // Alg. 1: predicted experts that are already cached are dropped ...
@@ -444,12 +448,15 @@ spmoe_status start_worker(spmoe_ctx* c) {
     if (c->worker.joinable()) return SPMOE_OK;
     const int pk = std::max(c->cfg.pred_k, 1), Tm = c->cfg.max_tokens;
     c->q_load.resize(kLoadQueueSlots);
+    // An entry that an earlier, failed attempt already filled is kept (stop_worker frees whatever exists).
     for (auto& t : c->q_load) {
-        HIP_TRY(c, hipMalloc(&t.dev_idx, sizeof(int32_t) * Tm * pk));
-        HIP_TRY(c, hipMalloc(&t.dev_p, sizeof(float) * Tm * pk));
-        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&t.host_idx), sizeof(int32_t) * Tm * pk, hipHostMallocDefault));
-        HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&t.host_p), sizeof(float) * Tm * pk, hipHostMallocDefault));
-        HIP_TRY(c, hipEventCreateWithFlags(&t.ev, hipEventDisableTiming));
+        if (!t.dev_idx) HIP_TRY(c, hipMalloc(&t.dev_idx, sizeof(int32_t) * Tm * pk));
+        if (!t.dev_p) HIP_TRY(c, hipMalloc(&t.dev_p, sizeof(float) * Tm * pk));
+        if (!t.host_idx)
+            HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&t.host_idx), sizeof(int32_t) * Tm * pk, hipHostMallocDefault));
+        if (!t.host_p)
+            HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&t.host_p), sizeof(float) * Tm * pk, hipHostMallocDefault));
+        if (!t.ev) HIP_TRY(c, hipEventCreateWithFlags(&t.ev, hipEventDisableTiming));
     }
     c->worker = std::thread(worker_main, c);
     return SPMOE_OK;

@@ -219,6 +219,25 @@ spmoe_status spmoe_prefetch_drain(spmoe_ctx* ctx);
  * does not depend on the cache state. */
 spmoe_status spmoe_moe_verify_layer(spmoe_ctx* ctx, int layer, const float* dev_x, int T, float* dev_out);
 
+/* The same layer for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): no context, no allocation of any kind, no host wait.
+ * Every routed and shared expert must already be in HBM: host_dev_blobs is a HOST array of
+ * n_experts + n_shared DEVICE pointers to packed blobs (routed experts 0..E-1, then the shared ones),
+ * dev_gate the layer's gate Wg[E][d] in weight_dtype; dev_x [T][d] and dev_out [T][d] are fp32 device
+ * memory, all 16-byte aligned; stream is a hipStream_t (NULL = default stream).  Of cfg only the shape
+ * fields, weight_dtype, renorm_topk and max_tokens (T <= max_tokens) are used.  The result is bit-identical
+ * to spmoe_moe_verify_layer with everything resident (same kernels, same summation order).
+ * The intermediates live in one fixed device array of SPMOE_STATIC_SCRATCH_BYTES per GPU, shared by all
+ * calls on that GPU: calls that may overlap on one GPU (different streams or threads) race and must be
+ * serialised by the caller.  SPMOE_ERANGE if this call needs more than the array holds, roughly
+ *   A*f*sizeof(weight) + splits*A*d*4 + 64 KiB,  A = T*(top_k + n_shared), splits <= 4 K-splits of the down GEMM
+ * (5.3 MB for d=6144, f=16384, top-2, T=32).  SPMOE_EINVAL for a bad configuration, NULL or misaligned
+ * pointers; SPMOE_EHIP if a launch fails.  Asynchronous on `stream`. */
+#define SPMOE_STATIC_SCRATCH_BYTES (16u << 20)
+spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg, void* stream, const void* dev_gate,
+                                             const void* const* host_dev_blobs, const float* dev_x, int T,
+                                             float* dev_out);
+
 /* ---- cutoff-layer policy ("Cutoff layer design") ----------------------------------------------*/
 
 /* Largest cutoff layer L in [0, n_layers) that satisfies the paper's two constraints with k_i

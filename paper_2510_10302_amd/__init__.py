@@ -7,5 +7,6 @@ not been built (``python -m paper_2510_10302_amd.build`` or ``__graft_entry__.bu
 """
 from .binding import (  # noqa: F401
     SpmoeError, Config, Context, Stats, ProfileRecord, expert_blob_bytes, pack_expert, lib_path, load_library, suggest_cutoff, gemm_plan,
+    moe_layer_resident_static,
     F32, BF16, DECLARED_SYMBOLS,
 )

@@ -23,7 +23,7 @@ DECLARED_SYMBOLS = [
     "spmoe_token_permutation", "spmoe_predict_experts", "spmoe_prefetch", "spmoe_moe_verify_layer",
     "spmoe_profile_begin", "spmoe_profile_collect", "spmoe_last_layer_kernel_ms",
     "spmoe_suggest_cutoff", "spmoe_measure_expert_load_ms", "spmoe_predict_prefetch_async", "spmoe_prefetch_drain",
-    "spmoe_gemm_plan",
+    "spmoe_gemm_plan", "spmoe_moe_layer_resident_static",
 ]
 
 
@@ -106,6 +106,7 @@ def load_library():
         "spmoe_predict_prefetch_async": (i32, [vp, i32, vp, i32]),
         "spmoe_prefetch_drain": (i32, [vp]),
         "spmoe_gemm_plan": (i32, [cp, i32, vp]),
+        "spmoe_moe_layer_resident_static": (i32, [cp, vp, vp, vp, vp, i32, vp]),
     }
     assert sorted(sig) == sorted(DECLARED_SYMBOLS)
     for name, (res, args) in sig.items():
@@ -159,6 +160,22 @@ def gemm_plan(cfg, projection):
     if st != 0:
         raise SpmoeError(st, "spmoe_gemm_plan")
     return dict(splits=out[0], k_waves=out[1], k_steps=out[2], n_sub=out[3], exact=bool(out[4]), lds_bytes=out[5])
+
+
+def moe_layer_resident_static(cfg, dev_gate, dev_blobs, dev_x, dev_out, stream=None):
+    """The resident verify layer without a context and without any allocation (fixed device scratch array).
+    dev_blobs: device tensors holding the packed routed experts 0..E-1, then the shared ones."""
+    import torch
+    lib = load_library()
+    if len(dev_blobs) != cfg.n_experts + cfg.n_shared:
+        raise ValueError("expected %d blobs" % (cfg.n_experts + cfg.n_shared))
+    ptrs = (ctypes.c_void_p * len(dev_blobs))(*[_dev_ptr(b) for b in dev_blobs])
+    stream = stream if stream is not None else torch.cuda.current_stream()
+    st = lib.spmoe_moe_layer_resident_static(ctypes.byref(cfg), ctypes.c_void_p(stream.cuda_stream), _dev_ptr(dev_gate),
+                                             ptrs, _dev_ptr(dev_x, torch.float32), dev_x.shape[0],
+                                             _dev_ptr(dev_out, torch.float32))
+    if st != 0:
+        raise SpmoeError(st, "spmoe_moe_layer_resident_static")
 
 
 def _host_ptr(buf):

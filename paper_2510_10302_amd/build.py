@@ -5,7 +5,8 @@ import subprocess
 _DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_DIR)
 LIB = os.path.join(_DIR, "libspmoe.so")
-SOURCES = [os.path.join(_DIR, "csrc", "spmoe_kernels.hip"), os.path.join(_DIR, "csrc", "spmoe_runtime.cpp")]
+SOURCES = [os.path.join(_DIR, "csrc", "spmoe_kernels.hip"), os.path.join(_DIR, "csrc", "spmoe_static.hip"),
+           os.path.join(_DIR, "csrc", "spmoe_runtime.cpp")]
 
 
 def build(verbose=False):

@@ -55,6 +55,8 @@ hipError_t spmoe_launch_down(hipStream_t stream, int dtype, const SpmoeShape& s,
                              const SpmoeRouting& r, const void* h, float* ypart, int splits, int32_t* steal);
 hipError_t spmoe_launch_combine(hipStream_t stream, const SpmoeShape& s, const SpmoeRouting& r, const float* ypart,
                                 int splits, float* out);
+// True if spmoe_create would accept the configuration; otherwise *why names the first offending field.
+bool spmoe_config_ok(const spmoe_config* cfg, const char** why);
 // Number of K-splits (partial-sum planes of ypart) the down projection uses for this shape.
 int spmoe_down_splits(int dtype, int d, int f);
 // plan of the bf16 expert GEMM of `projection` (0 gate/up, 1 down): splits, kw, ksw, nw, exact, LDS bytes

@@ -140,7 +140,9 @@ spmoe_status fail(spmoe_ctx* c, spmoe_status st, const char* fmt, ...) {
         if (e_ != hipSuccess) return fail((c), SPMOE_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
     } while (0)
 
-bool config_ok(const spmoe_config* c, const char** why) {
+}  // namespace
+
+bool spmoe_config_ok(const spmoe_config* c, const char** why) {
     if (!c) { *why = "config is NULL"; return false; }
     if (c->weight_dtype != SPMOE_F32 && c->weight_dtype != SPMOE_BF16) { *why = "weight_dtype"; return false; }
     if (c->n_layers < 1) { *why = "n_layers < 1"; return false; }
@@ -154,6 +156,10 @@ bool config_ok(const spmoe_config* c, const char** why) {
     if (c->pred_k < 0 || c->pred_k > SPMOE_MAX_TOPK || c->pred_k > c->n_experts) { *why = "pred_k out of range"; return false; }
     return true;
 }
+
+namespace {
+
+bool config_ok(const spmoe_config* c, const char** why) { return spmoe_config_ok(c, why); }
 
 size_t elem_bytes(int dtype) { return dtype == SPMOE_BF16 ? 2 : 4; }
 

@@ -24,10 +24,6 @@ struct SpmoeRouting {
     int32_t* idx;      // [Tmax][k]       selected experts, rank order
     float* w;          // [Tmax][k]       gating scores
     float* logits;     // [Tmax][E]
-    int32_t* counts;   // [E + n_shared]  assignments per expert
-    int32_t* offsets;  // [E + n_shared + 1]
-    int32_t* perm;     // [Tmax*k + n_shared*Tmax] assignment ids, expert by expert
-    int32_t* ticket;   // [1] arrival counter of the routing kernel, self-resetting
     int32_t* steal;    // [2] unit counters of the two expert GEMMs, zeroed by the routing kernel
 };
 
@@ -44,9 +40,7 @@ struct SpmoeShape {
 
 // Launchers (spmoe_kernels.hip).  All asynchronous on `stream`; return hipGetLastError().
 hipError_t spmoe_launch_gate_topk(hipStream_t stream, int dtype, const float* x, const void* wg, int T, int E, int d,
-                                  int k, int renorm, int32_t* idx, float* w, float* logits,
-                                  int n_shared, int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* ticket,
-                                  int32_t* steal);
+                                  int k, int renorm, int32_t* idx, float* w, float* logits, int32_t* steal);
 hipError_t spmoe_launch_permute(hipStream_t stream, const int32_t* idx, int T, int k, int E, int32_t* counts,
                                 int32_t* offsets, int32_t* perm);
 hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape& s, const SpmoeExpertList& list,

@@ -102,8 +102,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 #define GROUP_MAX_A (SPMOE_MAX_TOKENS * SPMOE_MAX_TOPK)   // 256 routed assignments at most
 
 __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n_shared, int32_t* counts,
-                                  int32_t* offsets, int32_t* perm, int* s_idx, int* s_cnt, int* s_scan,
-                                  int32_t* steal = nullptr) {
+                                  int32_t* offsets, int32_t* perm, int* s_idx, int* s_cnt, int* s_scan) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     const int A = T * k;
     const int E_tot = E + n_shared;
@@ -142,11 +141,12 @@ __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n
         perm[s_scan[e] + rank] = a;
     }
     for (int a = A + tid; a < A + n_shared * T; a += nthr) perm[a] = a;
-    if (steal != nullptr && tid < 2) steal[tid] = 0;   // unit counters of the two expert GEMMs that follow
 }
 
 // ---------------------------------------------------------------------------------------------
-// K1: gate logits + softmax + top-k (+ grouping by the last workgroup).  Grid = T, block = 256 (512 for E >= 32).
+// K1: gate logits + softmax + top-k.  Grid = T, block = 256 (512 for E >= 32).  The token-to-expert grouping
+// is not done here: every workgroup of the expert GEMMs derives it from idx in LDS (a few hundred integers),
+// which costs less than a second pass over all tokens behind a device-wide arrival counter would.
 // ---------------------------------------------------------------------------------------------
 // Raw 8-element weight chunk (16 bytes of bf16 or 32 bytes of fp32) and its dot product with 8 x values.
 template <typename WT> struct Chunk8;
@@ -221,18 +221,14 @@ template <typename WT>
 __global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict__ x, const WT* __restrict__ wg,
                                                         int T, int E, int d, int k, int renorm,
                                                         int32_t* __restrict__ idx_out, float* __restrict__ w_out,
-                                                        float* __restrict__ logits_out, int do_group, int n_shared,
-                                                        int32_t* counts, int32_t* offsets, int32_t* perm,
-                                                        int32_t* ticket, int32_t* steal) {
+                                                        float* __restrict__ logits_out, int32_t* steal) {
     __shared__ float s_logit[SPMOE_MAX_EXPERTS];
-    __shared__ int s_idx[GROUP_MAX_A];
-    __shared__ int s_cnt[512];
-    __shared__ int s_scan[256];
-    __shared__ int s_last;
 
     const int t = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* xt = x + (size_t)t * d;
+    // the unit counters of the two expert GEMMs that follow start at zero
+    if (steal != nullptr && t == 0 && tid < 2) steal[tid] = 0;
 
     // ---- gate logits: each wave scores `epw` experts per pass; all loads of a round (KI chunks of 8
     //      elements per lane, for every expert of the pass) are issued before the arithmetic starts
@@ -241,84 +237,67 @@ __global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict_
     else if (epw == 2) gate_logits_pass<WT, 2>(xt, wg, E, d, wave, lane, s_logit);
     else gate_logits_pass<WT, 1>(xt, wg, E, d, wave, lane, s_logit);
     __syncthreads();
+    if (wave != 0) return;
 
     // ---- wave 0: softmax and k rounds of wave-wide argmax (lane l owns experts l and l + 64)
-    if (wave == 0) {
-        float v[2];
-        bool taken[2];
-        float lmax = -INFINITY;
+    float v[2];
+    bool taken[2];
+    float lmax = -INFINITY;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int e = lane + 64 * q;
-            float l = (e < E) ? s_logit[e] : -INFINITY;
-            if (e < E && logits_out) logits_out[(size_t)t * E + e] = l;
-            if (!(l == l)) l = -INFINITY;            // NaN never wins
-            v[q] = l;
-            taken[q] = !(e < E);
-            lmax = fmaxf(lmax, l);
-        }
-        const float m = wave_max(lmax);
-        float psum = 0.f;
+    for (int q = 0; q < 2; ++q) {
+        const int e = lane + 64 * q;
+        float l = (e < E) ? s_logit[e] : -INFINITY;
+        if (e < E && logits_out) logits_out[(size_t)t * E + e] = l;
+        if (!(l == l)) l = -INFINITY;            // NaN never wins
+        v[q] = l;
+        taken[q] = !(e < E);
+        lmax = fmaxf(lmax, l);
+    }
+    const float m = wave_max(lmax);
+    float psum = 0.f;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) psum += (lane + 64 * q < E) ? expf(v[q] - m) : 0.f;
-        const float denom = wave_sum(psum);
+    for (int q = 0; q < 2; ++q) psum += (lane + 64 * q < E) ? expf(v[q] - m) : 0.f;
+    const float denom = wave_sum(psum);
 
-        int sel_i[SPMOE_MAX_TOPK];
-        float sel_p[SPMOE_MAX_TOPK];
-        float sel_sum = 0.f;
+    int sel_i[SPMOE_MAX_TOPK];
+    float sel_p[SPMOE_MAX_TOPK];
+    float sel_sum = 0.f;
 #pragma unroll
-        for (int r = 0; r < SPMOE_MAX_TOPK; ++r) {
-            sel_i[r] = 0; sel_p[r] = 0.f;
-            if (r < k) {
-                // best untaken candidate of this lane; the lower index wins a tie
-                float bv = -INFINITY;
-                int bi = INT_MAX;
+    for (int r = 0; r < SPMOE_MAX_TOPK; ++r) {
+        sel_i[r] = 0; sel_p[r] = 0.f;
+        if (r < k) {
+            // best untaken candidate of this lane; the lower index wins a tie
+            float bv = -INFINITY;
+            int bi = INT_MAX;
 #pragma unroll
-                for (int q = 1; q >= 0; --q)
-                    if (!taken[q] && (v[q] >= bv)) { bv = v[q]; bi = lane + 64 * q; }
-                const float best = wave_max(bi == INT_MAX ? -INFINITY : bv);
-                int win;
-                if (E <= 64) {
-                    // one expert per lane: the lowest set bit of the ballot is the lowest index
-                    const unsigned long long b = __builtin_amdgcn_ballot_w64(bi != INT_MAX && bv == best);
-                    win = b ? (__builtin_ctzll(b)) : INT_MAX;
-                } else {
-                    win = wave_min_i((bi != INT_MAX && bv == best) ? bi : INT_MAX);
-                }
-                if (win == INT_MAX) win = 0;          // cannot happen for k <= E; keeps the index in range
-                if ((win & 63) == lane) {
-                    if (win >> 6) taken[1] = true; else taken[0] = true;
-                }
-                const float p = expf(best - m) / denom;
-                sel_i[r] = win;
-                sel_p[r] = p;
-                sel_sum += p;
+            for (int q = 1; q >= 0; --q)
+                if (!taken[q] && (v[q] >= bv)) { bv = v[q]; bi = lane + 64 * q; }
+            const float best = wave_max(bi == INT_MAX ? -INFINITY : bv);
+            int win;
+            if (E <= 64) {
+                // one expert per lane: the lowest set bit of the ballot is the lowest index
+                const unsigned long long b = __builtin_amdgcn_ballot_w64(bi != INT_MAX && bv == best);
+                win = b ? (__builtin_ctzll(b)) : INT_MAX;
+            } else {
+                win = wave_min_i((bi != INT_MAX && bv == best) ? bi : INT_MAX);
             }
+            if (win == INT_MAX) win = 0;          // cannot happen for k <= E; keeps the index in range
+            if ((win & 63) == lane) {
+                if (win >> 6) taken[1] = true; else taken[0] = true;
+            }
+            const float p = expf(best - m) / denom;
+            sel_i[r] = win;
+            sel_p[r] = p;
+            sel_sum += p;
         }
-        if (lane == 0) {
+    }
+    // lane r writes the r-th selection (one store instruction for the whole row)
 #pragma unroll
-            for (int r = 0; r < SPMOE_MAX_TOPK; ++r)
-                if (r < k) {
-                    idx_out[(size_t)t * k + r] = sel_i[r];
-                    w_out[(size_t)t * k + r] = renorm ? sel_p[r] / sel_sum : sel_p[r];
-                }
+    for (int r = 0; r < SPMOE_MAX_TOPK; ++r)
+        if (r < k && lane == r) {
+            idx_out[(size_t)t * k + r] = sel_i[r];
+            w_out[(size_t)t * k + r] = renorm ? sel_p[r] / sel_sum : sel_p[r];
         }
-    }
-    if (!do_group) return;
-
-    // ---- the last workgroup to arrive groups all assignments by expert.  Thread 0 wrote this token's idx / w,
-    //      so it alone releases them (device-scope fence) before taking a ticket; the last workgroup reads every
-    //      token's idx with device-scope atomic loads after thread 0's acquire fence and the barrier.
-    if (tid == 0) {
-        __threadfence();
-        const int old = atomicAdd(ticket, 1);
-        s_last = (old == T - 1);
-        __threadfence();
-    }
-    __syncthreads();
-    if (!s_last) return;
-    group_assignments(idx_out, T, k, E, n_shared, counts, offsets, perm, s_idx, s_cnt, s_scan, steal);
-    if (tid == 0) *ticket = 0;
 }
 
 // Stand-alone grouping of a routing result (one workgroup).
@@ -361,13 +340,13 @@ enum { MODE_GU = 0, MODE_DOWN = 1 };
 #define GEMM_MAX_ASSIGN (SPMOE_MAX_TOKENS * (SPMOE_MAX_TOPK + SPMOE_MAX_SHARED))
 
 struct GemmParams {
-    const int32_t* offsets;
-    const int32_t* perm;
+    const int32_t* idx;   // [T][k] routing result: expert of assignment a = t*k + r
     const float* x;       // MODE_GU input  [T][d]
     uint16_t* h;          // [A_tot][f] bf16 bits: MODE_GU output, MODE_DOWN input
     float* ypart;         // MODE_DOWN output [splits][A_tot][d]
     int32_t T, k, d, f;
     int32_t A_tot;        // T*k + n_shared*T
+    int32_t E;            // routed experts
     int32_t E_tot;        // routed + shared experts
     int32_t ks_total;     // k-steps of the contraction: d/32 (GU), f/32 (DOWN)
     int32_t ks_split;     // k-steps per K-split
@@ -402,8 +381,11 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
     extern __shared__ float s_mem[];
     float* s_red = s_mem;                                 // [2][waves][NMAT][64 lanes][4]
     int* s_grp = reinterpret_cast<int*>(s_mem + 2 * p.waves * NMAT * 256);   // [GEMM_MAX_GROUPS + 1]
-    int* s_off = s_grp + GEMM_MAX_GROUPS + 1;             // [SPMOE_MAX_ETOT + 1] copy of offsets
-    int* s_perm = s_off + SPMOE_MAX_ETOT + 1;             // [GEMM_MAX_ASSIGN] copy of perm
+    int* s_base = s_grp + GEMM_MAX_GROUPS + 1;            // [SPMOE_MAX_ETOT] start of the expert's run in s_perm, -1: not in this launch
+    int* s_cnt = s_base + SPMOE_MAX_ETOT;                 // [SPMOE_MAX_ETOT] assignments of the expert
+    unsigned* s_mask = reinterpret_cast<unsigned*>(s_cnt + SPMOE_MAX_ETOT);   // [SPMOE_MAX_EXPERTS] bit t: token t chose the expert
+    int* s_idx = reinterpret_cast<int*>(s_mask + SPMOE_MAX_EXPERTS);          // [GROUP_MAX_A] expert of each routed assignment
+    int* s_perm = s_idx + GROUP_MAX_A;                    // [GEMM_MAX_ASSIGN] assignments expert by expert, in list order
     int* s_next = s_perm + GEMM_MAX_ASSIGN;               // [2] unit handed to the workgroup two iterations ahead
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -411,47 +393,27 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
     const int kslice = wave % p.kw, nsub = wave / p.kw;  // this wave's K slice and N sub-tile of the unit
     const int K = (MODE == MODE_GU) ? p.d : p.f;          // contraction length
     const int N = (MODE == MODE_GU) ? p.f : p.d;          // output features
+    const int upg = p.splits * p.n_tiles;                 // units per group
+    const int A = p.T * p.k;                              // routed assignments
 
-    // ---- routing tables into LDS (read again at every change of group), and the active groups of this
-    //      launch: (list entry, token tile) pairs with at least one token
-    for (int i = tid; i < p.A_tot; i += blockDim.x) s_perm[i] = p.perm[i];
-    for (int i = tid; i <= p.E_tot; i += blockDim.x) s_off[i] = p.offsets[i];
-    if (wave == 0) {
-        int base = 0;
-        for (int i0 = 0; i0 < list.n; i0 += 64) {
-            const int i = i0 + lane;
-            int tiles = 0;
-            if (i < list.n) {
-                const int e = list.id[i];
-                tiles = (p.offsets[e + 1] - p.offsets[e] + 15) >> 4;
-            }
-            int incl = tiles;                             // inclusive scan over the wave
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int v = __shfl_up(incl, off);
-                if (lane >= off) incl += v;
-            }
-            const int excl = incl - tiles;
-            for (int t = 0; t < tiles; ++t) s_grp[base + excl + t] = i * 2 + t;
-            base += __shfl(incl, 63);
-        }
-        if (lane == 0) s_grp[GEMM_MAX_GROUPS] = base;
+    // ---- token -> expert grouping, by every workgroup for itself (T <= 32 tokens, so one 32-bit mask per expert
+    //      says which tokens chose it: its popcount is the expert's load, the popcount below bit t the rank of
+    //      token t's assignment inside the expert -- a stable counting sort without a second pass over idx)
+    for (int e = tid; e < p.E_tot; e += blockDim.x) {
+        if (e < p.E) s_mask[e] = 0u;
+        s_base[e] = -1;
     }
     __syncthreads();
-    const int n_groups = s_grp[GEMM_MAX_GROUPS];
-    const int upg = p.splits * p.n_tiles;                 // units per group
-    const long long U = (long long)n_groups * upg;
-    // Unit schedule: the first units are cut into gridDim.x equal contiguous ranges; the last 1/dyn_div is handed
-    // out one unit at a time through an atomic counter, so workgroups that stream faster (the XCDs do not all
-    // see the same bandwidth) take more of it and all finish together.  Which workgroup computes a unit does
-    // not change its value.  A stolen unit usually costs a reload of the token tile, so the tail only pays
-    // where finish times spread widely.  Measured, that is the launches with one 8-wave workgroup per CU
-    // (down projection at d = 6144, f = 16384: 8 % faster); with 11- and 16-wave workgroups it changed the
-    // gate/up projection by -1 % ... +1 % and slowed the down projection by 3 %, so those keep the static split.
-    const bool dyn = p.steal != nullptr && (p.dyn_force || (U >= 10ll * gridDim.x && blockDim.x <= 512));
-    const int U_dyn = dyn ? (int)(U / p.dyn_div) : 0;
-    const int U_st = (int)U - U_dyn;
-    const int u0 = (int)((long long)U_st * blockIdx.x / gridDim.x), u1 = (int)((long long)U_st * (blockIdx.x + 1) / gridDim.x);
+    for (int a = tid; a < A; a += blockDim.x) {
+        const int e = min(max(p.idx[a], 0), p.E - 1);
+        s_idx[a] = e;
+        atomicOr(&s_mask[e], 1u << (a / p.k));
+    }
+    __syncthreads();
+    // ---- wave 0: the launch's experts in list order -> runs in s_perm, active groups (list entry, token tile of
+    //      <= 16 tokens), and the unit schedule of this workgroup
+    long long U = 0;
+    int U_dyn = 0, U_st = 0, u1 = 0;
     // thread 0 only: takes the next unit off the counter, -1 once they are all handed out
     auto grab = [&]() -> int {
         if (U_dyn == 0) return -1;
@@ -463,14 +425,46 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
         if (u < 0) return -1;
         return (u + 1 < u1) ? u + 1 : grab();
     };
-    if (tid == 0) {
-        const int first = (u0 < u1) ? u0 : grab();
-        s_next[0] = first;
-        s_next[1] = successor(first);
+    if (wave == 0) {
+        int base = 0;                                     // packed running totals: groups << 16 | assignments
+        for (int i0 = 0; i0 < list.n; i0 += 64) {
+            const int i = i0 + lane;
+            int e = 0, cnt = 0;
+            if (i < list.n) {
+                e = list.id[i];
+                cnt = (e < p.E) ? __builtin_popcount(s_mask[e]) : p.T;
+            }
+            const int tiles = (cnt + 15) >> 4;
+            const int both = (tiles << 16) | cnt;         // <= 2 tiles and <= 32 assignments per entry: no carry
+            const int excl = wave_inclusive_scan(both) - both + base;
+            if (i < list.n) {
+                s_base[e] = excl & 0xFFFF;
+                s_cnt[e] = cnt;
+                for (int t = 0; t < tiles; ++t) s_grp[(excl >> 16) + t] = i * 2 + t;
+            }
+            base = __builtin_amdgcn_readlane(excl + both, 63);
+        }
+        // Unit schedule: the first units are cut into gridDim.x equal contiguous ranges; the last 1/dyn_div is handed
+        // out one unit at a time through an atomic counter, so workgroups that stream faster (the XCDs do not all
+        // see the same bandwidth) take more of it and all finish together.  Which workgroup computes a unit does
+        // not change its value.  A stolen unit usually costs a reload of the token tile, so the tail only pays
+        // where finish times spread widely.  Measured, that is the launches with one 8-wave workgroup per CU
+        // (down projection at d = 6144, f = 16384: 8 % faster); with 11- and 16-wave workgroups it changed the
+        // gate/up projection by -1 % ... +1 % and slowed the down projection by 3 %, so those keep the static split.
+        U = (long long)(base >> 16) * upg;
+        const bool dyn = p.steal != nullptr && (p.dyn_force || (U >= 10ll * gridDim.x && blockDim.x <= 512));
+        U_dyn = dyn ? (int)(U / p.dyn_div) : 0;
+        U_st = (int)U - U_dyn;
+        const int u0 = (int)((long long)U_st * blockIdx.x / gridDim.x);
+        u1 = (int)((long long)U_st * (blockIdx.x + 1) / gridDim.x);
+        if (lane == 0) {
+            const int first = (u0 < u1) ? u0 : grab();
+            s_next[0] = first;
+            s_next[1] = successor(first);
+        }
     }
     __syncthreads();
     int cur = s_next[0], nxt = s_next[1];
-    __syncthreads();                                      // s_next is rewritten inside the loop
     if (cur < 0) return;                                  // uniform over the workgroup
 
     const bf16x8 zero8 = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
@@ -502,6 +496,20 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
         }
     }
 
+    // ---- while the first weight tiles are on their way: the runs of s_perm.  Routed assignments by rank inside
+    //      their expert, shared experts' assignments in token order (shared expert s owns A + s*T + t).
+    for (int a = tid; a < A; a += blockDim.x) {
+        const int e = s_idx[a];
+        const int b = s_base[e];
+        if (b >= 0) s_perm[b + __builtin_popcount(s_mask[e] & ((1u << (a / p.k)) - 1u))] = a;
+    }
+    for (int a = A + tid; a < p.A_tot; a += blockDim.x) {
+        const int sidx = (a - A) / p.T;
+        const int b = s_base[p.E + sidx];
+        if (b >= 0) s_perm[b + (a - A) - sidx * p.T] = a;
+    }
+    __syncthreads();                                      // also: s_next is rewritten inside the loop
+
     bf16x8 xr[KSW];
     int cur_gs = -1;                                      // group * splits + split held in xr
     int beg = 0, cnt = 0;
@@ -520,8 +528,8 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
             cur_gs = g * p.splits + s;
             const int gi = s_grp[g];
             const int e = list.id[gi >> 1];
-            beg = s_off[e] + 16 * (gi & 1);
-            cnt = min(16, s_off[e + 1] - beg);
+            beg = s_base[e] + 16 * (gi & 1);
+            cnt = min(16, s_cnt[e] - 16 * (gi & 1));
             const int ks_lo = s * p.ks_split + kslice * KSW;
             const int a_n = (n < cnt) ? s_perm[beg + n] : -1;
             a_out = (((tid & 255) >> 4) < cnt) ? s_perm[beg + ((tid & 255) >> 4)] : -1;
@@ -626,9 +634,27 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
 template <int MODE>
 __global__ __launch_bounds__(256) void expert_gemm_f32_kernel(const SpmoeExpertList list, const GemmParams p,
                                                               float* __restrict__ h32) {
+    __shared__ unsigned s_tokens;                  // bit t: token t chose this block's expert
+    __shared__ int s_asg[SPMOE_MAX_TOKENS];        // the expert's assignments, ascending
     const int li = blockIdx.y;
     const int e = list.id[li];
-    const int beg = p.offsets[e], end = p.offsets[e + 1];
+    const int routed = p.T * p.k;
+    // the assignments of this block's expert, straight from the routing result
+    if (threadIdx.x == 0) s_tokens = 0u;
+    __syncthreads();
+    if (e < p.E)
+        for (int a = threadIdx.x; a < routed; a += blockDim.x)
+            if (min(max(p.idx[a], 0), p.E - 1) == e) atomicOr(&s_tokens, 1u << (a / p.k));
+    __syncthreads();
+    const unsigned tokens = (e < p.E) ? s_tokens : (p.T >= 32 ? ~0u : ((1u << p.T) - 1u));
+    if (e < p.E) {
+        for (int a = threadIdx.x; a < routed; a += blockDim.x)
+            if (min(max(p.idx[a], 0), p.E - 1) == e) s_asg[__builtin_popcount(tokens & ((1u << (a / p.k)) - 1u))] = a;
+    } else if ((int)threadIdx.x < p.T) {
+        s_asg[threadIdx.x] = routed + (e - p.E) * p.T + threadIdx.x;
+    }
+    __syncthreads();
+    const int beg = 0, end = __builtin_popcount(tokens);
     if (end <= beg) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int K = (MODE == MODE_GU) ? p.d : p.f;
@@ -638,7 +664,6 @@ __global__ __launch_bounds__(256) void expert_gemm_f32_kernel(const SpmoeExpertL
     const float* blob = static_cast<const float*>(list.blob[li]);
     const float* w0 = (MODE == MODE_GU) ? blob + (size_t)row * K : blob + (size_t)2 * p.d * p.f + (size_t)row * K;
     const float* w1 = blob + (size_t)p.d * p.f + (size_t)row * K;   // W_up row (MODE_GU only)
-    const int routed = p.T * p.k;
 
     for (int c = beg; c < end; c += 8) {
         float a0[8], a1[8];
@@ -647,7 +672,7 @@ __global__ __launch_bounds__(256) void expert_gemm_f32_kernel(const SpmoeExpertL
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             a0[i] = 0.f; a1[i] = 0.f;
-            asg[i] = (c + i < end) ? p.perm[c + i] : -1;
+            asg[i] = (c + i < end) ? s_asg[c + i] : -1;
             const int a = max(asg[i], 0);
             if (MODE == MODE_GU) {
                 const int tok = a < routed ? a / p.k : (a - routed) % p.T;
@@ -716,16 +741,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 // launchers
 // ---------------------------------------------------------------------------------------------
 hipError_t spmoe_launch_gate_topk(hipStream_t stream, int dtype, const float* x, const void* wg, int T, int E, int d,
-                                  int k, int renorm, int32_t* idx, float* w, float* logits, int n_shared,
-                                  int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* ticket, int32_t* steal) {
-    const int do_group = counts != nullptr;
+                                  int k, int renorm, int32_t* idx, float* w, float* logits, int32_t* steal) {
     const int threads = (E >= 32) ? 512 : 256;
     if (dtype == SPMOE_BF16)
         hipLaunchKernelGGL(gate_topk_kernel<uint16_t>, dim3(T), dim3(threads), 0, stream, x, static_cast<const uint16_t*>(wg),
-                           T, E, d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket, steal);
+                           T, E, d, k, renorm, idx, w, logits, steal);
     else
         hipLaunchKernelGGL(gate_topk_kernel<float>, dim3(T), dim3(threads), 0, stream, x, static_cast<const float*>(wg), T, E,
-                           d, k, renorm, idx, w, logits, do_group, n_shared, counts, offsets, perm, ticket, steal);
+                           d, k, renorm, idx, w, logits, steal);
     return hipGetLastError();
 }
 
@@ -808,7 +831,7 @@ int spmoe_down_splits(int dtype, int d, int f) {
 
 static size_t gemm_lds_bytes(int waves) {
     return (size_t)2 * waves * 2 * 256 * sizeof(float) +
-           (GEMM_MAX_GROUPS + 1 + SPMOE_MAX_ETOT + 1 + GEMM_MAX_ASSIGN + 2) * sizeof(int);
+           (GEMM_MAX_GROUPS + 1 + 2 * SPMOE_MAX_ETOT + SPMOE_MAX_EXPERTS + GROUP_MAX_A + GEMM_MAX_ASSIGN + 2) * sizeof(int);
 }
 
 void spmoe_describe_plan(int projection, int d, int f, int32_t out[6]) {
@@ -866,13 +889,13 @@ static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, con
 
 static GemmParams make_params(const SpmoeShape& s, const SpmoeRouting& r) {
     GemmParams p;
-    p.offsets = r.offsets;
-    p.perm = r.perm;
+    p.idx = r.idx;
     p.x = nullptr;
     p.h = nullptr;
     p.ypart = nullptr;
     p.T = s.T; p.k = s.k; p.d = s.d; p.f = s.f;
     p.A_tot = s.T * s.k + s.n_shared * s.T;
+    p.E = s.E;
     p.E_tot = s.E + s.n_shared;
     p.ks_total = 0; p.ks_split = 0; p.splits = 1; p.n_tiles = 0;
     p.waves = 4; p.kw = 4; p.nw = 1;

@@ -94,7 +94,7 @@ struct spmoe_ctx {
     int a_tot_max = 0;
 
     // pinned host staging for the few integers the host needs
-    int32_t* host_counts = nullptr;   // [E]
+    int32_t* host_idx = nullptr;      // [Tmax * top_k] routing of the current verify batch
     int32_t* host_pred_idx = nullptr; // [Tmax * pred_k]
     float* host_pred_p = nullptr;     // [Tmax * pred_k]
     hipEvent_t host_ready = nullptr;
@@ -388,8 +388,7 @@ spmoe_status launch_prediction(spmoe_ctx* c, int layer, const float* dev_draft_x
     spmoe_status st = span_begin(c, c->compute, 3, layer, n, &span);
     if (st != SPMOE_OK) return st;
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_draft_x, c->layers[layer].gate, n,
-                                      c->cfg.n_experts, c->cfg.d_model, pk, 0, dev_idx, dev_p, nullptr, 0, nullptr, nullptr,
-                                      nullptr, nullptr, nullptr));
+                                      c->cfg.n_experts, c->cfg.d_model, pk, 0, dev_idx, dev_p, nullptr, nullptr));
     HIP_TRY(c, hipMemcpyAsync(host_idx, dev_idx, sizeof(int32_t) * n * pk, hipMemcpyDeviceToHost, c->compute));
     HIP_TRY(c, hipMemcpyAsync(host_p, dev_p, sizeof(float) * n * pk, hipMemcpyDeviceToHost, c->compute));
     return span_end(c, c->compute, span);
@@ -599,21 +598,16 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
         if ((e = hipMalloc(&r.idx, sizeof(int32_t) * Tm * k)) != hipSuccess) return e;
         if ((e = hipMalloc(&r.w, sizeof(float) * Tm * k)) != hipSuccess) return e;
         if ((e = hipMalloc(&r.logits, sizeof(float) * Tm * E)) != hipSuccess) return e;
-        if ((e = hipMalloc(&r.counts, sizeof(int32_t) * E_tot)) != hipSuccess) return e;
-        if ((e = hipMalloc(&r.offsets, sizeof(int32_t) * (E_tot + 1))) != hipSuccess) return e;
-        if ((e = hipMalloc(&r.perm, sizeof(int32_t) * (Tm * k + cfg->n_shared * Tm))) != hipSuccess) return e;
-        if ((e = hipMalloc(&r.ticket, sizeof(int32_t))) != hipSuccess) return e;
         if ((e = hipMalloc(&r.steal, 2 * sizeof(int32_t))) != hipSuccess) return e;
-        // the arrival counter must be zero before the first routing kernel: clear it on the compute stream
+        // the routing kernel zeroes the unit counters before every layer; start them at zero all the same
         if ((e = hipMemsetAsync(r.steal, 0, 2 * sizeof(int32_t), c->compute)) != hipSuccess) return e;
-        if ((e = hipMemsetAsync(r.ticket, 0, sizeof(int32_t), c->compute)) != hipSuccess) return e;
         return hipStreamSynchronize(c->compute);
     };
     CREATE_TRY(alloc_routing(c->route, cfg->top_k));
     CREATE_TRY(alloc_routing(c->pred, pk));
     CREATE_TRY(hipMalloc(&c->h, (size_t)c->a_tot_max * cfg->d_ff * (cfg->weight_dtype == SPMOE_BF16 ? 2 : 4)));
     CREATE_TRY(hipMalloc(&c->ypart, sizeof(float) * (size_t)c->down_splits * c->a_tot_max * cfg->d_model));
-    CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->host_counts), sizeof(int32_t) * E_tot, hipHostMallocDefault));
+    CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->host_idx), sizeof(int32_t) * Tm * cfg->top_k, hipHostMallocDefault));
     CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->host_pred_idx), sizeof(int32_t) * Tm * pk, hipHostMallocDefault));
     CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->host_pred_p), sizeof(float) * Tm * pk, hipHostMallocDefault));
 
@@ -659,14 +653,13 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
         for (auto& p : L.shared_dev) if (p) (void)hipFree(p);
     }
     auto free_routing = [](SpmoeRouting& r) {
-        (void)hipFree(r.idx); (void)hipFree(r.w); (void)hipFree(r.logits); (void)hipFree(r.counts);
-        (void)hipFree(r.offsets); (void)hipFree(r.perm); (void)hipFree(r.ticket); (void)hipFree(r.steal);
+        (void)hipFree(r.idx); (void)hipFree(r.w); (void)hipFree(r.logits); (void)hipFree(r.steal);
     };
     free_routing(c->route);
     free_routing(c->pred);
     (void)hipFree(c->h);
     (void)hipFree(c->ypart);
-    if (c->host_counts) (void)hipHostFree(c->host_counts);
+    if (c->host_idx) (void)hipHostFree(c->host_idx);
     if (c->host_pred_idx) (void)hipHostFree(c->host_pred_idx);
     if (c->host_pred_p) (void)hipHostFree(c->host_pred_p);
     if (c->host_ready) (void)hipEventDestroy(c->host_ready);
@@ -830,8 +823,7 @@ spmoe_status spmoe_gate_topk(spmoe_ctx* c, int layer, const float* dev_x, int T,
     if (!aligned16(dev_x)) return fail(c, SPMOE_EINVAL, "dev_x is not 16-byte aligned");
     if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_x, c->layers[layer].gate, T, c->cfg.n_experts,
-                                      c->cfg.d_model, k, c->cfg.renorm_topk, dev_idx, dev_w, dev_logits, 0, nullptr,
-                                      nullptr, nullptr, nullptr, nullptr));
+                                      c->cfg.d_model, k, c->cfg.renorm_topk, dev_idx, dev_w, dev_logits, nullptr));
     return SPMOE_OK;
 }
 
@@ -961,8 +953,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
     st = span_begin(c, c->compute, 5, layer, 0, &k1span);
     if (st != SPMOE_OK) return st;
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, dt, dev_x, L.gate, T, E, c->cfg.d_model, c->cfg.top_k,
-                                      c->cfg.renorm_topk, c->route.idx, c->route.w, c->route.logits, c->cfg.n_shared,
-                                      c->route.counts, c->route.offsets, c->route.perm, c->route.ticket, c->route.steal));
+                                      c->cfg.renorm_topk, c->route.idx, c->route.w, c->route.logits, c->route.steal));
     st = span_end(c, c->compute, k1span);
     if (st != SPMOE_OK) return st;
     kernel_mark(c, 1);
@@ -982,13 +973,16 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
         st = launch_experts(c, layer, sh, list, dev_x, true);
         if (st != SPMOE_OK) return st;
     } else {
-        // offloaded experts: the per-expert token counts decide which experts this batch needs
-        HIP_TRY(c, hipMemcpyAsync(c->host_counts, c->route.counts, sizeof(int32_t) * E, hipMemcpyDeviceToHost, c->compute));
+        // offloaded experts: the routing result (T * k expert ids) decides which experts this batch needs
+        const int n_asg = T * c->cfg.top_k;
+        HIP_TRY(c, hipMemcpyAsync(c->host_idx, c->route.idx, sizeof(int32_t) * n_asg, hipMemcpyDeviceToHost, c->compute));
         HIP_TRY(c, hipEventRecord(c->host_ready, c->compute));
         HIP_TRY(c, hipEventSynchronize(c->host_ready));
+        bool needed[SPMOE_MAX_EXPERTS] = {false};
+        for (int a = 0; a < n_asg; ++a) needed[std::min(std::max(c->host_idx[a], 0), E - 1)] = true;
         std::vector<int> hits, misses;
         for (int e = 0; e < E; ++e) {
-            if (c->host_counts[e] <= 0) continue;
+            if (!needed[e]) continue;
             if (L.slot_of[e] >= 0) hits.push_back(e);
             else {
                 if (!L.host_blob[e]) return fail(c, SPMOE_ESTATE, "expert %d of layer %d is needed but not registered", e, layer);

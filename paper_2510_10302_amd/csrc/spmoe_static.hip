@@ -1,7 +1,7 @@
 // spmoe_moe_layer_resident_static: the verify layer with every expert resident, for callers that cannot
 // allocate device memory.  It runs the same four kernels as spmoe_moe_verify_layer; what that entry point
-// keeps in buffers allocated by spmoe_create (routing tables, the arrival and unit counters, the intermediate
-// h and the K-split partial outputs) lives here in one file-scope device array.
+// keeps in buffers allocated by spmoe_create (the routing result, the unit counters, the intermediate h and the
+// K-split partial outputs) lives here in one file-scope device array.
 #include <hip/hip_runtime.h>
 
 #include <mutex>
@@ -35,13 +35,6 @@ hipError_t scratch_address(unsigned char** out) {
     return hipSuccess;
 }
 
-// The counters must be zero when the routing kernel starts.  A fill kernel rather than a memset, so that a
-// caller may record the call into a HIP graph.
-__global__ void clear_counters_kernel(int32_t* p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
-
 size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 }  // namespace
@@ -61,19 +54,18 @@ extern "C" spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg,
     for (int e = 0; e < E_tot; ++e)
         if (!host_dev_blobs[e] || misaligned(host_dev_blobs[e])) return SPMOE_EINVAL;
 
-    // carve the array: counters first, then the routing tables, h and the partial outputs of this call's T
+    // carve the array: unit counters first, then the routing result, h and the partial outputs of this call's T.
+    // Nothing in it has to survive from call to call: the routing kernel zeroes the two counters (with plain
+    // stores, so the call can be recorded into a HIP graph) and every other byte is written before it is read.
     const int dt = cfg->weight_dtype;
     const int splits = spmoe_down_splits(dt, d, f);
     const size_t A_tot = (size_t)T * k + (size_t)n_shared * T;
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off += round256(bytes); return at; };
-    const size_t o_counters = take(3 * sizeof(int32_t));            // ticket, two unit counters
+    const size_t o_counters = take(2 * sizeof(int32_t));
     const size_t o_idx = take(sizeof(int32_t) * T * k);
     const size_t o_w = take(sizeof(float) * T * k);
     const size_t o_logits = take(sizeof(float) * T * E);
-    const size_t o_counts = take(sizeof(int32_t) * E_tot);
-    const size_t o_offsets = take(sizeof(int32_t) * (E_tot + 1));
-    const size_t o_perm = take(sizeof(int32_t) * A_tot);
     const size_t o_h = take(A_tot * f * (dt == SPMOE_BF16 ? 2 : 4));
     const size_t o_ypart = take(sizeof(float) * splits * A_tot * d);
     if (off > (size_t)SPMOE_STATIC_SCRATCH_BYTES) return SPMOE_ERANGE;
@@ -85,14 +77,10 @@ extern "C" spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg,
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     SpmoeRouting r;
-    r.ticket = reinterpret_cast<int32_t*>(base + o_counters);
-    r.steal = r.ticket + 1;
+    r.steal = reinterpret_cast<int32_t*>(base + o_counters);
     r.idx = reinterpret_cast<int32_t*>(base + o_idx);
     r.w = reinterpret_cast<float*>(base + o_w);
     r.logits = reinterpret_cast<float*>(base + o_logits);
-    r.counts = reinterpret_cast<int32_t*>(base + o_counts);
-    r.offsets = reinterpret_cast<int32_t*>(base + o_offsets);
-    r.perm = reinterpret_cast<int32_t*>(base + o_perm);
     void* h = base + o_h;
     float* ypart = reinterpret_cast<float*>(base + o_ypart);
 
@@ -102,10 +90,8 @@ extern "C" spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg,
     for (int e = 0; e < E; ++e) { list.id[list.n] = (uint16_t)e; list.blob[list.n] = host_dev_blobs[e]; list.n += 1; }
     const SpmoeShape sh{T, k, E, n_shared, d, f};
 
-    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, st, r.ticket, 3);
-    if (hipGetLastError() != hipSuccess) return SPMOE_EHIP;
-    if (spmoe_launch_gate_topk(st, dt, dev_x, dev_gate, T, E, d, k, cfg->renorm_topk, r.idx, r.w, r.logits, n_shared,
-                               r.counts, r.offsets, r.perm, r.ticket, r.steal) != hipSuccess) return SPMOE_EHIP;
+    if (spmoe_launch_gate_topk(st, dt, dev_x, dev_gate, T, E, d, k, cfg->renorm_topk, r.idx, r.w, r.logits, r.steal) !=
+        hipSuccess) return SPMOE_EHIP;
     if (spmoe_launch_gate_up(st, dt, sh, list, r, dev_x, h, r.steal) != hipSuccess) return SPMOE_EHIP;
     if (spmoe_launch_down(st, dt, sh, list, r, h, ypart, splits, r.steal + 1) != hipSuccess) return SPMOE_EHIP;
     if (spmoe_launch_combine(st, sh, r, ypart, splits, dev_out) != hipSuccess) return SPMOE_EHIP;

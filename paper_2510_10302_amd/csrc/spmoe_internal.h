@@ -24,6 +24,7 @@ struct SpmoeRouting {
     int32_t* idx;      // [Tmax][k]       selected experts, rank order
     float* w;          // [Tmax][k]       gating scores
     float* logits;     // [Tmax][E]
+    void* xb;          // [Tmax][d]       the batch's hidden states rounded to bf16 (written by the routing kernel)
     int32_t* steal;    // [2] unit counters of the two expert GEMMs, zeroed by the routing kernel
 };
 
@@ -40,7 +41,7 @@ struct SpmoeShape {
 
 // Launchers (spmoe_kernels.hip).  All asynchronous on `stream`; return hipGetLastError().
 hipError_t spmoe_launch_gate_topk(hipStream_t stream, int dtype, const float* x, const void* wg, int T, int E, int d,
-                                  int k, int renorm, int32_t* idx, float* w, float* logits, int32_t* steal);
+                                  int k, int renorm, int32_t* idx, float* w, float* logits, int32_t* steal, void* xb);
 hipError_t spmoe_launch_permute(hipStream_t stream, const int32_t* idx, int T, int k, int E, int32_t* counts,
                                 int32_t* offsets, int32_t* perm);
 hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape& s, const SpmoeExpertList& list,
@@ -51,9 +52,11 @@ hipError_t spmoe_launch_combine(hipStream_t stream, const SpmoeShape& s, const S
                                 int splits, float* out);
 // True if spmoe_create would accept the configuration; otherwise *why names the first offending field.
 bool spmoe_config_ok(const spmoe_config* cfg, const char** why);
-// Number of K-splits (partial-sum planes of ypart) the down projection uses for this shape.
-int spmoe_down_splits(int dtype, int d, int f);
-// plan of the bf16 expert GEMM of `projection` (0 gate/up, 1 down): splits, kw, ksw, nw, exact, LDS bytes
-void spmoe_describe_plan(int projection, int d, int f, int32_t out[6]);
+// Number of K-splits (partial-sum planes of ypart) the down projection uses for this shape and batch size
+// (batches of more than 16 tokens use other instances of the kernel, which may split differently).
+int spmoe_down_splits(int dtype, int d, int f, int T);
+// plan of the bf16 expert GEMM of `projection` (0 gate/up, 1 down) for a batch of T tokens:
+// splits, kw, ksw, nw, exact, LDS bytes
+void spmoe_describe_plan(int projection, int d, int f, int T, int32_t out[6]);
 
 #endif

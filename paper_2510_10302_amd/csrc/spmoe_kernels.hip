@@ -19,6 +19,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "spmoe_internal.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -175,9 +177,10 @@ template <> struct Chunk8<float> {
 };
 
 // logits[e] = sum_j x[j] * Wg[e][j] for the experts of this wave: EPW experts per pass and wave.
+// xb_row (may be NULL): wave 0 also stores its x chunks rounded to bf16 there, for the expert GEMMs' token tiles.
 template <typename WT, int EPW>
 __device__ __forceinline__ void gate_logits_pass(const float* __restrict__ xt, const WT* __restrict__ wg, int E, int d,
-                                                 int wave, int lane, float* s_logit) {
+                                                 int wave, int lane, float* s_logit, uint16_t* __restrict__ xb_row) {
     constexpr int KI = (sizeof(WT) == 2 ? 16 : 8) / EPW;      // chunks per lane and round
     const int nwaves = blockDim.x >> 6;
     for (int e0 = wave * EPW; e0 < E; e0 += nwaves * EPW) {
@@ -196,6 +199,15 @@ __device__ __forceinline__ void gate_logits_pass(const float* __restrict__ xt, c
 #pragma unroll
                     for (int q = 0; q < EPW; ++q)
                         if (e0 + q < E) w[i][q].load(wg + (size_t)(e0 + q) * d + j);
+                }
+            }
+            if (xb_row != nullptr && e0 == 0) {          // wave 0, its first pass: every chunk of the row once
+#pragma unroll
+                for (int i = 0; i < KI; ++i) {
+                    const int j = jb + (i * 64 + lane) * 8;
+                    if (j < d)
+                        *reinterpret_cast<u32x4*>(xb_row + j) = u32x4{pack_bf16x2(xa[i].x, xa[i].y), pack_bf16x2(xa[i].z, xa[i].w),
+                                                                      pack_bf16x2(xb[i].x, xb[i].y), pack_bf16x2(xb[i].z, xb[i].w)};
                 }
             }
 #pragma unroll
@@ -221,7 +233,8 @@ template <typename WT>
 __global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict__ x, const WT* __restrict__ wg,
                                                         int T, int E, int d, int k, int renorm,
                                                         int32_t* __restrict__ idx_out, float* __restrict__ w_out,
-                                                        float* __restrict__ logits_out, int32_t* steal) {
+                                                        float* __restrict__ logits_out, int32_t* steal,
+                                                        uint16_t* __restrict__ xb_out) {
     __shared__ float s_logit[SPMOE_MAX_EXPERTS];
 
     const int t = blockIdx.x;
@@ -233,9 +246,10 @@ __global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict_
     // ---- gate logits: each wave scores `epw` experts per pass; all loads of a round (KI chunks of 8
     //      elements per lane, for every expert of the pass) are issued before the arithmetic starts
     const int epw = (E >= 16) ? 4 : (E >= 8 ? 2 : 1);
-    if (epw == 4) gate_logits_pass<WT, 4>(xt, wg, E, d, wave, lane, s_logit);
-    else if (epw == 2) gate_logits_pass<WT, 2>(xt, wg, E, d, wave, lane, s_logit);
-    else gate_logits_pass<WT, 1>(xt, wg, E, d, wave, lane, s_logit);
+    uint16_t* xb_row = (xb_out != nullptr && wave == 0) ? xb_out + (size_t)t * d : nullptr;
+    if (epw == 4) gate_logits_pass<WT, 4>(xt, wg, E, d, wave, lane, s_logit, xb_row);
+    else if (epw == 2) gate_logits_pass<WT, 2>(xt, wg, E, d, wave, lane, s_logit, xb_row);
+    else gate_logits_pass<WT, 1>(xt, wg, E, d, wave, lane, s_logit, xb_row);
     __syncthreads();
     if (wave != 0) return;
 
@@ -341,7 +355,8 @@ enum { MODE_GU = 0, MODE_DOWN = 1 };
 
 struct GemmParams {
     const int32_t* idx;   // [T][k] routing result: expert of assignment a = t*k + r
-    const float* x;       // MODE_GU input  [T][d]
+    const float* x;       // MODE_GU input  [T][d] (fp32-weight kernels)
+    const uint16_t* xb;   // MODE_GU input  [T][d] rounded to bf16 by the routing kernel (MFMA kernels)
     uint16_t* h;          // [A_tot][f] bf16 bits: MODE_GU output, MODE_DOWN input
     float* ypart;         // MODE_DOWN output [splits][A_tot][d]
     int32_t T, k, d, f;
@@ -369,9 +384,9 @@ constexpr int ring_depth(int ksw, int limit) {
     return best;
 }
 
-template <int MODE, int KSW, bool EXACT>
-__global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list,
-                                                                                const GemmParams p) {
+template <int MODE, int KSW, bool EXACT, int NTOK>
+__global__ __launch_bounds__(((KSW > 14 || NTOK == 2) ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list,
+                                                                                               const GemmParams p) {
     // Two weight tiles are in flight per k-step: gate and up tile of one N-tile (adjacent KiB) in MODE_GU,
     // the tiles of two consecutive N-tiles in MODE_DOWN (ks_total KiB apart); both share the B operand.
     constexpr int NMAT = 2;
@@ -379,16 +394,19 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
     constexpr int STEP = (MODE == MODE_GU) ? 128 : 64;    // 16-byte units between consecutive k-steps of a stream
     const size_t soff = (MODE == MODE_GU) ? 64 : (size_t)p.ks_total * 64;   // second stream's offset
     extern __shared__ float s_mem[];
-    float* s_red = s_mem;                                 // [2][waves][NMAT][64 lanes][4]
-    int* s_grp = reinterpret_cast<int*>(s_mem + 2 * p.waves * NMAT * 256);   // [GEMM_MAX_GROUPS + 1]
+    float* s_red = s_mem;                                 // [2][waves][NMAT][NTOK][64 lanes][4]
+    const void** s_blob = reinterpret_cast<const void**>(s_mem + 2 * p.waves * NMAT * NTOK * 256);   // [SPMOE_MAX_ETOT] copy of list.blob
+    int* s_grp = reinterpret_cast<int*>(s_blob + SPMOE_MAX_ETOT);             // [GEMM_MAX_GROUPS + 1]
     int* s_base = s_grp + GEMM_MAX_GROUPS + 1;            // [SPMOE_MAX_ETOT] start of the expert's run in s_perm, -1: not in this launch
     int* s_cnt = s_base + SPMOE_MAX_ETOT;                 // [SPMOE_MAX_ETOT] assignments of the expert
     unsigned* s_mask = reinterpret_cast<unsigned*>(s_cnt + SPMOE_MAX_ETOT);   // [SPMOE_MAX_EXPERTS] bit t: token t chose the expert
     int* s_idx = reinterpret_cast<int*>(s_mask + SPMOE_MAX_EXPERTS);          // [GROUP_MAX_A] expert of each routed assignment
     int* s_perm = s_idx + GROUP_MAX_A;                    // [GEMM_MAX_ASSIGN] assignments expert by expert, in list order
     int* s_next = s_perm + GEMM_MAX_ASSIGN;               // [2] unit handed to the workgroup two iterations ahead
+    int* s_lid = s_next + 2;                              // [SPMOE_MAX_ETOT] copy of list.id
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform over the wave: keeps unit addressing in SGPRs
     const int n = lane & 15, kg = lane >> 4;
     const int kslice = wave % p.kw, nsub = wave / p.kw;  // this wave's K slice and N sub-tile of the unit
     const int K = (MODE == MODE_GU) ? p.d : p.f;          // contraction length
@@ -399,15 +417,31 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
     // ---- token -> expert grouping, by every workgroup for itself (T <= 32 tokens, so one 32-bit mask per expert
     //      says which tokens chose it: its popcount is the expert's load, the popcount below bit t the rank of
     //      token t's assignment inside the expert -- a stable counting sort without a second pass over idx)
+    //      Everything the prologue needs from global memory is requested at once: the routing result and the
+    //      launch list (kernel arguments indexed at run time are memory loads too).
+    int ev[4];                                            // A <= 256 assignments, >= 64 threads
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int a = tid + q * blockDim.x;
+        ev[q] = (a < A) ? p.idx[a] : 0;
+    }
+    for (int i = tid; i < list.n; i += blockDim.x) {
+        s_lid[i] = list.id[i];
+        s_blob[i] = list.blob[i];
+    }
     for (int e = tid; e < p.E_tot; e += blockDim.x) {
         if (e < p.E) s_mask[e] = 0u;
         s_base[e] = -1;
     }
     __syncthreads();
-    for (int a = tid; a < A; a += blockDim.x) {
-        const int e = min(max(p.idx[a], 0), p.E - 1);
-        s_idx[a] = e;
-        atomicOr(&s_mask[e], 1u << (a / p.k));
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int a = tid + q * blockDim.x;
+        if (a < A) {
+            const int e = min(max(ev[q], 0), p.E - 1);
+            s_idx[a] = e;
+            atomicOr(&s_mask[e], 1u << (a / p.k));
+        }
     }
     __syncthreads();
     // ---- wave 0: the launch's experts in list order -> runs in s_perm, active groups (list entry, token tile of
@@ -431,10 +465,11 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
             const int i = i0 + lane;
             int e = 0, cnt = 0;
             if (i < list.n) {
-                e = list.id[i];
+                e = s_lid[i];
                 cnt = (e < p.E) ? __builtin_popcount(s_mask[e]) : p.T;
             }
-            const int tiles = (cnt + 15) >> 4;
+            // NTOK = 1: a group is a tile of <= 16 of the expert's tokens; NTOK = 2: all (<= 32) of them
+            const int tiles = (NTOK == 2) ? (cnt > 0 ? 1 : 0) : ((cnt + 15) >> 4);
             const int both = (tiles << 16) | cnt;         // <= 2 tiles and <= 32 assignments per entry: no carry
             const int excl = wave_inclusive_scan(both) - both + base;
             if (i < list.n) {
@@ -478,7 +513,7 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
         const int ks_lo = s * p.ks_split + kslice * KSW;
         const int ks_hi = min(min(ks_lo + KSW, (s + 1) * p.ks_split), p.ks_total);
         nks = EXACT ? KSW : max(ks_hi - ks_lo, 0);
-        const char* blob = static_cast<const char*>(list.blob[li]) + region;
+        const char* blob = static_cast<const char*>(s_blob[li]) + region;
         const size_t sub = (size_t)nt * p.nw + nsub;                                   // this wave's sub-tile
         const size_t tile = (MODE == MODE_GU) ? sub : 2 * sub;                        // its first weight tile
         return reinterpret_cast<const bf16x8*>(blob) + (tile * p.ks_total + ks_lo) * STEP + lane;
@@ -508,13 +543,20 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
         const int b = s_base[p.E + sidx];
         if (b >= 0) s_perm[b + (a - A) - sidx * p.T] = a;
     }
-    __syncthreads();                                      // also: s_next is rewritten inside the loop
+    // LDS writes done, then workgroup barrier (s_next is rewritten inside the loop); the weight loads keep flying
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
     bf16x8 xr[KSW];
     int cur_gs = -1;                                      // group * splits + split held in xr
     int beg = 0, cnt = 0;
     int a_out = -1;                                       // assignment this thread writes in the epilogue
     int buf = 0;
+    // NTOK = 2 only: the B operand of the group's second token tile (tokens 16..31) does not fit in registers
+    // beside the first one; it is re-read for every unit, k-step by k-step, through a small ring of its own.  It
+    // is the same KSW KiB per wave for every unit of a group, so these loads hit in the L2 and cost no HBM traffic.
+    bf16x8 ring1[NTOK == 2 ? PF : 1];
+    const uint16_t* brow1 = nullptr;                      // this lane's row of the second tile, NULL: no such token
+    bool two = false;                                     // the current group has more than 16 tokens
 
     for (int it = 0; cur >= 0; ++it) {
         const int u = cur;
@@ -527,34 +569,40 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
         if (g * p.splits + s != cur_gs) {
             cur_gs = g * p.splits + s;
             const int gi = s_grp[g];
-            const int e = list.id[gi >> 1];
+            const int e = s_lid[gi >> 1];
             beg = s_base[e] + 16 * (gi & 1);
-            cnt = min(16, s_cnt[e] - 16 * (gi & 1));
+            cnt = min(16 * NTOK, s_cnt[e] - 16 * (gi & 1));
             const int ks_lo = s * p.ks_split + kslice * KSW;
-            const int a_n = (n < cnt) ? s_perm[beg + n] : -1;
-            a_out = (((tid & 255) >> 4) < cnt) ? s_perm[beg + ((tid & 255) >> 4)] : -1;
-            if (MODE == MODE_GU) {
-                const int routed = p.T * p.k;
-                const int tok = (a_n < 0) ? 0 : (a_n < routed ? a_n / p.k : (a_n - routed) % p.T);
-                const float* xrow = p.x + (size_t)tok * K + ks_lo * 32 + kg * 8;
+            const int a_n = (n < min(cnt, 16)) ? s_perm[beg + n] : -1;
+            {   // the output this thread writes first in the epilogue: token (tid & 255) >> 4 of tile tid >> 8
+                const int tok = ((NTOK == 2) ? (tid >> 8) * 16 : 0) + ((tid & 255) >> 4);
+                a_out = (tok < cnt && ((tid & 255) >> 4) < 16) ? s_perm[beg + tok] : -1;
+            }
+            // rows of the B operand: the token's hidden state (rounded to bf16 by the routing kernel) for gate/up,
+            // the assignment's intermediate h for down
+            const int routed = p.T * p.k;
+            auto row_of = [&](int a) -> int {
+                if (a < 0) return 0;
+                if (MODE == MODE_DOWN) return a;
+                return a < routed ? a / p.k : (a - routed) % p.T;
+            };
+            const uint16_t* bsrc = ((MODE == MODE_GU) ? p.xb : p.h) + ks_lo * 32 + kg * 8;
+            const uint16_t* brow = bsrc + (size_t)row_of(a_n) * K;
 #pragma unroll
-                for (int j = 0; j < KSW; ++j) {
-                    u32x4 packed = {0u, 0u, 0u, 0u};
-                    if (a_n >= 0 && (EXACT || j < nks)) {
-                        const float4 lo = *reinterpret_cast<const float4*>(xrow + j * 32);
-                        const float4 hi = *reinterpret_cast<const float4*>(xrow + j * 32 + 4);
-                        packed[0] = pack_bf16x2(lo.x, lo.y); packed[1] = pack_bf16x2(lo.z, lo.w);
-                        packed[2] = pack_bf16x2(hi.x, hi.y); packed[3] = pack_bf16x2(hi.z, hi.w);
-                    }
-                    xr[j] = __builtin_bit_cast(bf16x8, packed);
-                }
-            } else {
-                const uint16_t* hrow = p.h + (size_t)max(a_n, 0) * K + ks_lo * 32 + kg * 8;
+            for (int j = 0; j < KSW; ++j) {
+                u32x4 packed = {0u, 0u, 0u, 0u};
+                if (a_n >= 0 && (EXACT || j < nks)) packed = *reinterpret_cast<const u32x4*>(brow + j * 32);
+                xr[j] = __builtin_bit_cast(bf16x8, packed);
+            }
+            if (NTOK == 2) {
+                two = cnt > 16;
+                const int a_1 = (two && n < cnt - 16) ? s_perm[beg + 16 + n] : -1;
+                brow1 = (a_1 >= 0) ? bsrc + (size_t)row_of(a_1) * K : nullptr;
 #pragma unroll
-                for (int j = 0; j < KSW; ++j) {
+                for (int j = 0; j < PF; ++j) {
                     u32x4 packed = {0u, 0u, 0u, 0u};
-                    if (a_n >= 0 && (EXACT || j < nks)) packed = *reinterpret_cast<const u32x4*>(hrow + j * 32);
-                    xr[j] = __builtin_bit_cast(bf16x8, packed);
+                    if (brow1 != nullptr && (EXACT || j < nks)) packed = *reinterpret_cast<const u32x4*>(brow1 + j * 32);
+                    ring1[NTOK == 2 ? j : 0] = __builtin_bit_cast(bf16x8, packed);
                 }
             }
         }
@@ -562,57 +610,87 @@ __global__ __launch_bounds__((KSW > 14 ? 8 : 16) * 64) void expert_gemm_kernel(c
         // ---- stream the unit's KSW k-steps; the ring refills from this unit, then from the next one
         int nks_next = 0;
         const bf16x8* wp_next = (nxt >= 0) ? unit_ptr(nxt, nks_next) : nullptr;
-        f32x4 acc[NMAT];
+        f32x4 acc[NMAT], acc1[NMAT];
 #pragma unroll
-        for (int m = 0; m < NMAT; ++m) acc[m] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int m = 0; m < NMAT; ++m) { acc[m] = f32x4{0.f, 0.f, 0.f, 0.f}; acc1[m] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        // one straight-line MFMA chain per case (a branch per k-step would sit between the MFMAs)
+        auto k_steps = [&](auto second_tile) __attribute__((always_inline)) {
+            constexpr bool SECOND = decltype(second_tile)::value;
 #pragma unroll
-        for (int j = 0; j < KSW; ++j) {
-            bf16x8 a[NMAT];
+            for (int j = 0; j < KSW; ++j) {
+                bf16x8 a[NMAT];
 #pragma unroll
-            for (int m = 0; m < NMAT; ++m) a[m] = ring[j % PF][m];
-            if (j + PF < KSW) {
+                for (int m = 0; m < NMAT; ++m) a[m] = ring[j % PF][m];
+                if (j + PF < KSW) {
 #pragma unroll
-                for (int m = 0; m < NMAT; ++m) {
-                    ring[j % PF][m] = zero8;
-                    if (EXACT || j + PF < nks)
-                        ring[j % PF][m] = __builtin_nontemporal_load(wp + (size_t)(j + PF) * STEP + m * soff);
+                    for (int m = 0; m < NMAT; ++m) {
+                        ring[j % PF][m] = zero8;
+                        if (EXACT || j + PF < nks)
+                            ring[j % PF][m] = __builtin_nontemporal_load(wp + (size_t)(j + PF) * STEP + m * soff);
+                    }
+                } else {
+#pragma unroll
+                    for (int m = 0; m < NMAT; ++m) {
+                        ring[j % PF][m] = zero8;
+                        if (wp_next != nullptr && (EXACT || j + PF - KSW < nks_next))
+                            ring[j % PF][m] = __builtin_nontemporal_load(wp_next + (size_t)(j + PF - KSW) * STEP + m * soff);
+                    }
                 }
-            } else {
 #pragma unroll
-                for (int m = 0; m < NMAT; ++m) {
-                    ring[j % PF][m] = zero8;
-                    if (wp_next != nullptr && (EXACT || j + PF - KSW < nks_next))
-                        ring[j % PF][m] = __builtin_nontemporal_load(wp_next + (size_t)(j + PF - KSW) * STEP + m * soff);
+                for (int m = 0; m < NMAT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], xr[j], acc[m], 0, 0, 0);
+                if (SECOND) {
+                    // second tile: the same weight tiles against tokens 16..31.  Its operand ring refills from the
+                    // same rows: later steps of this unit, then the first steps again for the next unit (a change
+                    // of group or K-split reloads them above).
+                    const bf16x8 b1 = ring1[NTOK == 2 ? j % PF : 0];
+                    const int jn = (j + PF < KSW) ? j + PF : j + PF - KSW;
+                    u32x4 packed = {0u, 0u, 0u, 0u};
+                    if (brow1 != nullptr && (EXACT || jn < nks)) packed = *reinterpret_cast<const u32x4*>(brow1 + jn * 32);
+                    ring1[NTOK == 2 ? j % PF : 0] = __builtin_bit_cast(bf16x8, packed);
+#pragma unroll
+                    for (int m = 0; m < NMAT; ++m) acc1[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], b1, acc1[m], 0, 0, 0);
                 }
             }
-#pragma unroll
-            for (int m = 0; m < NMAT; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], xr[j], acc[m], 0, 0, 0);
-        }
+        };
+        if (NTOK == 2 && two) k_steps(std::true_type{});
+        else k_steps(std::false_type{});
         wp = wp_next;
         nks = nks_next;
 
         // ---- cross-wave reduction through LDS (buffer `buf`), summed in wave order
-        float* red = s_red + buf * (p.waves * NMAT * 256);
+        float* red = s_red + buf * (p.waves * NMAT * NTOK * 256);
 #pragma unroll
-        for (int m = 0; m < NMAT; ++m) *reinterpret_cast<f32x4*>(red + ((wave * NMAT + m) * 64 + lane) * 4) = acc[m];
+        for (int m = 0; m < NMAT; ++m) {
+            *reinterpret_cast<f32x4*>(red + (((wave * NMAT + m) * NTOK) * 64 + lane) * 4) = acc[m];
+            if (NTOK == 2 && two) *reinterpret_cast<f32x4*>(red + (((wave * NMAT + m) * NTOK + 1) * 64 + lane) * 4) = acc1[m];
+        }
         if (tid == 0) s_next[it & 1] = succ;
         // LDS writes done, then workgroup barrier; outstanding weight loads keep flying across it
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         cur = nxt;
         nxt = s_next[it & 1];
-        // o -> (sub-tile, token on, feature fi), consecutive threads on consecutive features; small workgroups
-        // take several outputs per thread.  The kw partial sums of a sub-tile are added in wave order.
-        for (int o = tid; o < 256 * p.nw; o += blockDim.x) {
+        // o -> (sub-tile or token tile, token on, feature fi), consecutive threads on consecutive features; small
+        // workgroups take several outputs per thread.  The kw partial sums of a sub-tile are added in wave order.
+        // (NTOK = 2 launches have one N sub-tile; `sub` then is the token tile.)
+        for (int o = tid; o < 256 * (NTOK == 2 ? (two ? 2 : 1) : p.nw); o += blockDim.x) {
             const int sub = o >> 8, fi = o & 15, on = (o & 255) >> 4;
-            if (on >= cnt) continue;
-            const int a_o = (o == tid) ? a_out : s_perm[beg + on];
+            const int tok = (NTOK == 2) ? sub * 16 + on : on;        // position in the group
+            if (tok >= cnt) continue;
+            const int a_o = (o == tid) ? a_out : s_perm[beg + tok];
             const int src = (((fi >> 2) * 16 + on) * 4) + (fi & 3);
             float s0 = 0.f, s1 = 0.f;
-            for (int w = sub * p.kw; w < (sub + 1) * p.kw; ++w) {
-                s0 += red[(w * NMAT) * 256 + src];
-                s1 += red[(w * NMAT + 1) * 256 + src];
+            if (NTOK == 2) {
+                for (int w = 0; w < p.kw; ++w) {
+                    s0 += red[((w * NMAT) * NTOK + sub) * 256 + src];
+                    s1 += red[((w * NMAT + 1) * NTOK + sub) * 256 + src];
+                }
+            } else {
+                for (int w = sub * p.kw; w < (sub + 1) * p.kw; ++w) {
+                    s0 += red[(w * NMAT) * 256 + src];
+                    s1 += red[(w * NMAT + 1) * 256 + src];
+                }
             }
-            const int st = nt * p.nw + sub;               // sub-tile index along N
+            const int st = (NTOK == 2) ? nt : nt * p.nw + sub;     // sub-tile index along N
             if (MODE == MODE_GU) {
                 const float hval = (s0 / (1.f + expf(-s0))) * s1;
                 p.h[(size_t)a_o * N + st * 16 + fi] = (uint16_t)f32_to_bf16_bits(hval);
@@ -741,14 +819,14 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 // launchers
 // ---------------------------------------------------------------------------------------------
 hipError_t spmoe_launch_gate_topk(hipStream_t stream, int dtype, const float* x, const void* wg, int T, int E, int d,
-                                  int k, int renorm, int32_t* idx, float* w, float* logits, int32_t* steal) {
+                                  int k, int renorm, int32_t* idx, float* w, float* logits, int32_t* steal, void* xb) {
     const int threads = (E >= 32) ? 512 : 256;
     if (dtype == SPMOE_BF16)
         hipLaunchKernelGGL(gate_topk_kernel<uint16_t>, dim3(T), dim3(threads), 0, stream, x, static_cast<const uint16_t*>(wg),
-                           T, E, d, k, renorm, idx, w, logits, steal);
+                           T, E, d, k, renorm, idx, w, logits, steal, static_cast<uint16_t*>(xb));
     else
         hipLaunchKernelGGL(gate_topk_kernel<float>, dim3(T), dim3(threads), 0, stream, x, static_cast<const float*>(wg), T, E,
-                           d, k, renorm, idx, w, logits, steal);
+                           d, k, renorm, idx, w, logits, steal, static_cast<uint16_t*>(nullptr));
     return hipGetLastError();
 }
 
@@ -777,14 +855,39 @@ static bool is_exact_ksw(int ksw) {
 static bool plan_ok(int waves, int ksw) { return waves >= 1 && waves <= 16 && (ksw <= 14 || waves <= 8); }
 
 // ks_total: k-steps of the contraction; n_units: N-tiles (GU) or N-tile pairs (DOWN); env: optional override
-// "splits,kw,ksw,nw" (tuning aid).
-static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char* env) {
+// "splits,kw,ksw,nw" (tuning aid).  two_tiles: plan for the instances that take up to 32 tokens of an expert in
+// one pass over its weights (batches of more than 16 tokens): at most 8 waves, one N sub-tile.
+// k-steps per wave the two-tile instances can hold in registers (256 VGPRs at 8 waves per workgroup): the second
+// tile's ring and accumulators come on top of the first tile's KSW * 4 registers.
+constexpr int two_tile_max_ksw(int mode) { return mode == MODE_GU ? 24 : 16; }
+
+static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char* env, bool two_tiles, int mode) {
     const char* force = getenv(env);
     if (force) {
         int s = 0, kw = 0, ksw = 0, nw = 0;
         if (sscanf(force, "%d,%d,%d,%d", &s, &kw, &ksw, &nw) == 4 && s >= 1 && s <= max_splits && nw >= 1 &&
-            s * kw * ksw == ks_total && n_units % nw == 0 && is_exact_ksw(ksw) && plan_ok(kw * nw, ksw))
+            s * kw * ksw == ks_total && n_units % nw == 0 && is_exact_ksw(ksw) && plan_ok(kw * nw, ksw) &&
+            (!two_tiles || (kw <= 8 && nw == 1 && ksw <= two_tile_max_ksw(mode))))
             return GemmPlan{s, kw, ksw, nw, true};
+    }
+    if (two_tiles) {
+        // 8 waves first (most bytes in flight), fewest K-splits, then anything exact with at least 4 waves
+        static const int kKswTwo[] = {16, 24, 12, 14, 8, 28, 32, 11, 10, 4};
+        for (int min_kw : {8, 4, 1}) {
+            for (int splits = 1; splits <= max_splits; splits *= 2) {
+                if (ks_total % splits) break;
+                const int per = ks_total / splits;
+                for (int ksw : kKswTwo) {
+                    if (per % ksw || ksw > two_tile_max_ksw(mode)) continue;
+                    const int kw = per / ksw;
+                    if (kw >= min_kw && kw <= 8) return GemmPlan{splits, kw, ksw, 1, true};
+                }
+            }
+        }
+        int splits = 1;
+        while ((ks_total + splits - 1) / splits > 8 * 32) ++splits;
+        const int per = (ks_total + splits - 1) / splits;
+        return GemmPlan{splits, (per + 31) / 32, 32, 1, false};
     }
     // preference (measured, the differences are small): as few K-splits as possible, one N sub-tile, 9..16 waves
     static const int kKswPreference[] = {12, 8, 11, 14, 16, 4, 10, 24, 28, 32};
@@ -821,23 +924,25 @@ static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char*
     return GemmPlan{splits, (per + 31) / 32, 32, 1, false};
 }
 
-static GemmPlan plan_gate_up(int d, int f) { return plan_gemm(d / 32, f / 16, 1, "SPMOE_PLAN_GATE_UP"); }
-static GemmPlan plan_down(int d, int f) { return plan_gemm(f / 32, d / 32, 4, "SPMOE_PLAN_DOWN"); }
+static GemmPlan plan_gate_up(int d, int f, bool two) { return plan_gemm(d / 32, f / 16, 1, "SPMOE_PLAN_GATE_UP", two, MODE_GU); }
+static GemmPlan plan_down(int d, int f, bool two) { return plan_gemm(f / 32, d / 32, 4, "SPMOE_PLAN_DOWN", two, MODE_DOWN); }
 
-int spmoe_down_splits(int dtype, int d, int f) {
+int spmoe_down_splits(int dtype, int d, int f, int T) {
     if (dtype != SPMOE_BF16) return 1;
-    return plan_down(d, f).splits;
+    return plan_down(d, f, T > 16).splits;
 }
 
-static size_t gemm_lds_bytes(int waves) {
-    return (size_t)2 * waves * 2 * 256 * sizeof(float) +
-           (GEMM_MAX_GROUPS + 1 + 2 * SPMOE_MAX_ETOT + SPMOE_MAX_EXPERTS + GROUP_MAX_A + GEMM_MAX_ASSIGN + 2) * sizeof(int);
+static size_t gemm_lds_bytes(int waves, int ntok) {
+    return (size_t)2 * waves * 2 * ntok * 256 * sizeof(float) +
+           (GEMM_MAX_GROUPS + 1 + 2 * SPMOE_MAX_ETOT + SPMOE_MAX_EXPERTS + GROUP_MAX_A + GEMM_MAX_ASSIGN + 2 + SPMOE_MAX_ETOT) *
+               sizeof(int) +
+           SPMOE_MAX_ETOT * sizeof(void*);
 }
 
-void spmoe_describe_plan(int projection, int d, int f, int32_t out[6]) {
-    const GemmPlan p = projection == 0 ? plan_gate_up(d, f) : plan_down(d, f);
+void spmoe_describe_plan(int projection, int d, int f, int T, int32_t out[6]) {
+    const GemmPlan p = projection == 0 ? plan_gate_up(d, f, T > 16) : plan_down(d, f, T > 16);
     out[0] = p.splits; out[1] = p.kw; out[2] = p.ksw; out[3] = p.nw; out[4] = p.exact ? 1 : 0;
-    out[5] = (int32_t)gemm_lds_bytes(p.waves());
+    out[5] = (int32_t)gemm_lds_bytes(p.waves(), T > 16 ? 2 : 1);
 }
 
 // Persistent grid size: as many workgroups as fit on the chip at once for this instance.
@@ -853,18 +958,21 @@ static int resident_blocks(Kernel kernel, int threads, size_t lds) {
     return cus * per_cu;
 }
 
-template <int MODE>
+template <int MODE, int NTOK>
 static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, const SpmoeExpertList& list,
                                    const GemmParams& p) {
     const int threads = plan.waves() * 64;
-    const size_t lds = gemm_lds_bytes(plan.waves());
+    const size_t lds = gemm_lds_bytes(plan.waves(), NTOK);
     // cache of grid sizes per (instance, waves): [exact ksw index or generic][waves]
-    static int grid_cache[2][16][17];
-#define SPMOE_GEMM_CASE(SLOT_, KSW_, EXACT_)                                                                    \
-    {                                                                                                           \
-        int& g = grid_cache[MODE][SLOT_][plan.waves()];                                                           \
-        if (g == 0) g = resident_blocks(expert_gemm_kernel<MODE, KSW_, EXACT_>, threads, lds);                  \
-        hipLaunchKernelGGL((expert_gemm_kernel<MODE, KSW_, EXACT_>), dim3(g), dim3(threads), lds, stream, list, p); \
+    static int grid_cache[16][17];
+    // (two-tile instances exist only up to the k-step count their registers hold; the plans never ask for others)
+#define SPMOE_GEMM_CASE(SLOT_, KSW_, EXACT_)                                                                          \
+    if constexpr (NTOK == 1 || !(EXACT_) || KSW_ <= two_tile_max_ksw(MODE)) {                                         \
+        int& g = grid_cache[SLOT_][plan.waves()];                                                                     \
+        if (g == 0) g = resident_blocks(expert_gemm_kernel<MODE, KSW_, EXACT_, NTOK>, threads, lds);                  \
+        hipLaunchKernelGGL((expert_gemm_kernel<MODE, KSW_, EXACT_, NTOK>), dim3(g), dim3(threads), lds, stream, list, p); \
+    } else {                                                                                                          \
+        return hipErrorInvalidValue;                                                                                  \
     }
     if (plan.exact) {
         switch (plan.ksw) {
@@ -890,6 +998,7 @@ static hipError_t launch_gemm_bf16(hipStream_t stream, const GemmPlan& plan, con
 static GemmParams make_params(const SpmoeShape& s, const SpmoeRouting& r) {
     GemmParams p;
     p.idx = r.idx;
+    p.xb = static_cast<const uint16_t*>(r.xb);
     p.x = nullptr;
     p.h = nullptr;
     p.ypart = nullptr;
@@ -919,13 +1028,14 @@ hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape&
     p.x = x;
     p.h = static_cast<uint16_t*>(h);
     if (dtype == SPMOE_BF16) {
-        const GemmPlan plan = plan_gate_up(s.d, s.f);
+        const bool two = s.T > 16;        // more than 16 tokens: an expert may get up to 32, taken in one pass
+        const GemmPlan plan = plan_gate_up(s.d, s.f, two);
         p.ks_total = s.d / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
         p.splits = plan.splits;
         p.n_tiles = s.f / 16 / plan.nw;
         p.waves = plan.waves(); p.kw = plan.kw; p.nw = plan.nw;
-        return launch_gemm_bf16<MODE_GU>(stream, plan, list, p);
+        return two ? launch_gemm_bf16<MODE_GU, 2>(stream, plan, list, p) : launch_gemm_bf16<MODE_GU, 1>(stream, plan, list, p);
     }
     hipLaunchKernelGGL(expert_gemm_f32_kernel<MODE_GU>, dim3((s.f + 3) / 4, list.n), dim3(256), 0, stream, list, p,
                        static_cast<float*>(h));
@@ -940,14 +1050,15 @@ hipError_t spmoe_launch_down(hipStream_t stream, int dtype, const SpmoeShape& s,
     p.h = static_cast<uint16_t*>(const_cast<void*>(h));
     p.ypart = ypart;
     if (dtype == SPMOE_BF16) {
-        const GemmPlan plan = plan_down(s.d, s.f);
+        const bool two = s.T > 16;
+        const GemmPlan plan = plan_down(s.d, s.f, two);
         if (plan.splits != splits) return hipErrorInvalidValue;
         p.ks_total = s.f / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
         p.splits = plan.splits;
         p.n_tiles = s.d / 32 / plan.nw;
         p.waves = plan.waves(); p.kw = plan.kw; p.nw = plan.nw;
-        return launch_gemm_bf16<MODE_DOWN>(stream, plan, list, p);
+        return two ? launch_gemm_bf16<MODE_DOWN, 2>(stream, plan, list, p) : launch_gemm_bf16<MODE_DOWN, 1>(stream, plan, list, p);
     }
     hipLaunchKernelGGL(expert_gemm_f32_kernel<MODE_DOWN>, dim3((s.d + 3) / 4, list.n), dim3(256), 0, stream, list, p,
                        static_cast<float*>(const_cast<void*>(h)));

@@ -90,7 +90,7 @@ struct spmoe_ctx {
     SpmoeRouting pred{};          // routing scratch of spmoe_predict_experts
     void* h = nullptr;            // [A_tot_max][f] bf16 (fp32 for fp32 weights)
     float* ypart = nullptr;       // [splits][A_tot_max][d]
-    int down_splits = 1;
+    int down_splits = 1;          // planes of ypart (the largest K-split count any batch size uses)
     int a_tot_max = 0;
 
     // pinned host staging for the few integers the host needs
@@ -292,7 +292,8 @@ spmoe_status launch_experts(spmoe_ctx* c, int layer, const SpmoeShape& sh, const
     int32_t* steal = first_after_routing ? c->route.steal : nullptr;
     HIP_TRY(c, spmoe_launch_gate_up(c->compute, c->cfg.weight_dtype, sh, list, c->route, x, c->h, steal));
     if (timed) HIP_TRY(c, hipEventRecord(k2.end, c->compute));
-    HIP_TRY(c, spmoe_launch_down(c->compute, c->cfg.weight_dtype, sh, list, c->route, c->h, c->ypart, c->down_splits,
+    HIP_TRY(c, spmoe_launch_down(c->compute, c->cfg.weight_dtype, sh, list, c->route, c->h, c->ypart,
+                                 spmoe_down_splits(c->cfg.weight_dtype, sh.d, sh.f, sh.T),
                                  steal ? steal + 1 : nullptr));
     if (timed) {
         HIP_TRY(c, hipEventRecord(k3.end, c->compute));
@@ -388,7 +389,7 @@ spmoe_status launch_prediction(spmoe_ctx* c, int layer, const float* dev_draft_x
     spmoe_status st = span_begin(c, c->compute, 3, layer, n, &span);
     if (st != SPMOE_OK) return st;
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_draft_x, c->layers[layer].gate, n,
-                                      c->cfg.n_experts, c->cfg.d_model, pk, 0, dev_idx, dev_p, nullptr, nullptr));
+                                      c->cfg.n_experts, c->cfg.d_model, pk, 0, dev_idx, dev_p, nullptr, nullptr, nullptr));
     HIP_TRY(c, hipMemcpyAsync(host_idx, dev_idx, sizeof(int32_t) * n * pk, hipMemcpyDeviceToHost, c->compute));
     HIP_TRY(c, hipMemcpyAsync(host_p, dev_p, sizeof(float) * n * pk, hipMemcpyDeviceToHost, c->compute));
     return span_end(c, c->compute, span);
@@ -560,7 +561,9 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
     const int E = cfg->n_experts, S = cfg->cache_slots_per_layer, Tm = cfg->max_tokens;
     const int E_tot = E + cfg->n_shared;
     c->a_tot_max = Tm * cfg->top_k + cfg->n_shared * Tm;
-    c->down_splits = spmoe_down_splits(cfg->weight_dtype, cfg->d_model, cfg->d_ff);
+    // ypart holds one plane per K-split of the down projection; batches of at most 16 and of more tokens may split differently
+    c->down_splits = std::max(spmoe_down_splits(cfg->weight_dtype, cfg->d_model, cfg->d_ff, 1),
+                              spmoe_down_splits(cfg->weight_dtype, cfg->d_model, cfg->d_ff, Tm));
 
 #define CREATE_TRY(call)                                                             \
     do {                                                                             \
@@ -598,6 +601,7 @@ spmoe_status spmoe_create(const spmoe_config* cfg, void* compute_stream, spmoe_c
         if ((e = hipMalloc(&r.idx, sizeof(int32_t) * Tm * k)) != hipSuccess) return e;
         if ((e = hipMalloc(&r.w, sizeof(float) * Tm * k)) != hipSuccess) return e;
         if ((e = hipMalloc(&r.logits, sizeof(float) * Tm * E)) != hipSuccess) return e;
+        if ((e = hipMalloc(&r.xb, sizeof(uint16_t) * Tm * cfg->d_model)) != hipSuccess) return e;
         if ((e = hipMalloc(&r.steal, 2 * sizeof(int32_t))) != hipSuccess) return e;
         // the routing kernel zeroes the unit counters before every layer; start them at zero all the same
         if ((e = hipMemsetAsync(r.steal, 0, 2 * sizeof(int32_t), c->compute)) != hipSuccess) return e;
@@ -653,7 +657,7 @@ spmoe_status spmoe_destroy(spmoe_ctx* c) {
         for (auto& p : L.shared_dev) if (p) (void)hipFree(p);
     }
     auto free_routing = [](SpmoeRouting& r) {
-        (void)hipFree(r.idx); (void)hipFree(r.w); (void)hipFree(r.logits); (void)hipFree(r.steal);
+        (void)hipFree(r.idx); (void)hipFree(r.w); (void)hipFree(r.logits); (void)hipFree(r.xb); (void)hipFree(r.steal);
     };
     free_routing(c->route);
     free_routing(c->pred);
@@ -823,7 +827,7 @@ spmoe_status spmoe_gate_topk(spmoe_ctx* c, int layer, const float* dev_x, int T,
     if (!aligned16(dev_x)) return fail(c, SPMOE_EINVAL, "dev_x is not 16-byte aligned");
     if (!c->layers[layer].gate) return fail(c, SPMOE_ESTATE, "gate of layer %d not set", layer);
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, c->cfg.weight_dtype, dev_x, c->layers[layer].gate, T, c->cfg.n_experts,
-                                      c->cfg.d_model, k, c->cfg.renorm_topk, dev_idx, dev_w, dev_logits, nullptr));
+                                      c->cfg.d_model, k, c->cfg.renorm_topk, dev_idx, dev_w, dev_logits, nullptr, nullptr));
     return SPMOE_OK;
 }
 
@@ -953,7 +957,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
     st = span_begin(c, c->compute, 5, layer, 0, &k1span);
     if (st != SPMOE_OK) return st;
     HIP_TRY(c, spmoe_launch_gate_topk(c->compute, dt, dev_x, L.gate, T, E, c->cfg.d_model, c->cfg.top_k,
-                                      c->cfg.renorm_topk, c->route.idx, c->route.w, c->route.logits, c->route.steal));
+                                      c->cfg.renorm_topk, c->route.idx, c->route.w, c->route.logits, c->route.steal, c->route.xb));
     st = span_end(c, c->compute, k1span);
     if (st != SPMOE_OK) return st;
     kernel_mark(c, 1);
@@ -1046,7 +1050,7 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* c, int layer, const float* dev_x,
     size_t k4span;
     st = span_begin(c, c->compute, 6, layer, 0, &k4span);
     if (st != SPMOE_OK) return st;
-    HIP_TRY(c, spmoe_launch_combine(c->compute, sh, c->route, c->ypart, c->down_splits, dev_out));
+    HIP_TRY(c, spmoe_launch_combine(c->compute, sh, c->route, c->ypart, spmoe_down_splits(dt, sh.d, sh.f, sh.T), dev_out));
     st = span_end(c, c->compute, k4span);
     if (st != SPMOE_OK) return st;
     kernel_mark(c, 3);
@@ -1108,7 +1112,7 @@ spmoe_status spmoe_gemm_plan(const spmoe_config* cfg, int projection, int32_t ho
     const char* why;
     if (!config_ok(cfg, &why) || !host_plan_out || (projection != 0 && projection != 1)) return SPMOE_EINVAL;
     if (cfg->weight_dtype != SPMOE_BF16) return SPMOE_EINVAL;
-    spmoe_describe_plan(projection, cfg->d_model, cfg->d_ff, host_plan_out);
+    spmoe_describe_plan(projection, cfg->d_model, cfg->d_ff, cfg->max_tokens, host_plan_out);
     return SPMOE_OK;
 }
 

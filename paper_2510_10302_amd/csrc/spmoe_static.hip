@@ -58,7 +58,7 @@ extern "C" spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg,
     // Nothing in it has to survive from call to call: the routing kernel zeroes the two counters (with plain
     // stores, so the call can be recorded into a HIP graph) and every other byte is written before it is read.
     const int dt = cfg->weight_dtype;
-    const int splits = spmoe_down_splits(dt, d, f);
+    const int splits = spmoe_down_splits(dt, d, f, T);
     const size_t A_tot = (size_t)T * k + (size_t)n_shared * T;
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off += round256(bytes); return at; };
@@ -66,6 +66,7 @@ extern "C" spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg,
     const size_t o_idx = take(sizeof(int32_t) * T * k);
     const size_t o_w = take(sizeof(float) * T * k);
     const size_t o_logits = take(sizeof(float) * T * E);
+    const size_t o_xb = take(sizeof(uint16_t) * T * d);
     const size_t o_h = take(A_tot * f * (dt == SPMOE_BF16 ? 2 : 4));
     const size_t o_ypart = take(sizeof(float) * splits * A_tot * d);
     if (off > (size_t)SPMOE_STATIC_SCRATCH_BYTES) return SPMOE_ERANGE;
@@ -81,6 +82,7 @@ extern "C" spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg,
     r.idx = reinterpret_cast<int32_t*>(base + o_idx);
     r.w = reinterpret_cast<float*>(base + o_w);
     r.logits = reinterpret_cast<float*>(base + o_logits);
+    r.xb = base + o_xb;
     void* h = base + o_h;
     float* ypart = reinterpret_cast<float*>(base + o_ypart);
 
@@ -90,7 +92,7 @@ extern "C" spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg,
     for (int e = 0; e < E; ++e) { list.id[list.n] = (uint16_t)e; list.blob[list.n] = host_dev_blobs[e]; list.n += 1; }
     const SpmoeShape sh{T, k, E, n_shared, d, f};
 
-    if (spmoe_launch_gate_topk(st, dt, dev_x, dev_gate, T, E, d, k, cfg->renorm_topk, r.idx, r.w, r.logits, r.steal) !=
+    if (spmoe_launch_gate_topk(st, dt, dev_x, dev_gate, T, E, d, k, cfg->renorm_topk, r.idx, r.w, r.logits, r.steal, r.xb) !=
         hipSuccess) return SPMOE_EHIP;
     if (spmoe_launch_gate_up(st, dt, sh, list, r, dev_x, h, r.steal) != hipSuccess) return SPMOE_EHIP;
     if (spmoe_launch_down(st, dt, sh, list, r, h, ypart, splits, r.steal + 1) != hipSuccess) return SPMOE_EHIP;

@@ -214,6 +214,26 @@ def test_c5_mixtral_8x22b_layer_full_size(oracle32):
     L.close()
 
 
+@pytest.mark.parametrize("d,f,E,k,shared,T,rho", [
+    (6144, 16384, 8, 2, 0, 32, 0.98),   # configuration 5's layer, tokens of a sequence nearly parallel: experts with 17..32 tokens
+    (4096, 14336, 8, 2, 0, 24, 0.9),    # Mixtral-8x7B layer with a 24-token batch
+    (512, 1408, 16, 4, 2, 32, 0.97),    # shared experts always see all 32 tokens; ragged contraction (44 k-steps)
+    (256, 416, 4, 1, 0, 19, 0.99),      # 19 tokens, top-1: 18 on one expert, two of them in the second tile; generic plan (13 k-steps)
+])
+def test_experts_with_more_than_16_tokens_one_weight_pass(d, f, E, k, shared, T, rho, oracle32):
+    # batches of more than 16 tokens use the kernel instances that take up to 32 tokens of an expert in one pass
+    wl = _wl(d=d, f=f, E=E, k=k, shared=shared, dtype="bf16", layers=1, seed=9, gate_std=0.02 if d > 1024 else 0.05,
+             std=0.02 if d > 1024 else 0.05)
+    L = _loaded(wl, T)
+    x = si.hidden_correlated(9, T, d, rho, 1)
+    ref = oracle_layer(oracle32, wl, 0, x)
+    load = np.bincount(ref["idx"].reshape(-1), minlength=E)
+    assert load.max() > 16, "the seeded batch must overload an expert: %s" % load.tolist()
+    rep = check_layer(gpu_layer(L, 0, x), ref, k, REL_L2_BF16)
+    print((d, f, E, k, shared, T), "tokens per expert", load.tolist(), rep)
+    L.close()
+
+
 def test_c3_offloaded_stack_teacher_forced(oracle32):
     # benchmark configuration 3 (reduced to 3 layers, aliased backing): Mixtral-8x7B layers, experts in pinned host
     # memory, 3 cache slots per layer, draft noise sigma 0.5, cutoff layer 1; each layer is fed seeded x_l.

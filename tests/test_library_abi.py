@@ -137,12 +137,17 @@ def test_gemm_plans_fit_what_the_kernels_assume(sp):
     exact_steps = {4, 8, 10, 11, 12, 14, 16, 24, 28, 32}
     shapes = [(d, f) for d in range(32, 8193, 32) for f in (32, 64, 96, 1408, 4096, 6400, 14336, 16384)]
     shapes += [(d, f) for d in (32, 512, 2048, 4096, 6144, 8192) for f in range(32, 32769, 32)]
-    for d, f in shapes:
-        cfg = sp.Config(d_model=d, d_ff=f, n_experts=8, top_k=2, weight_dtype=sp.BF16)
+    for d, f, T in [(d, f, T) for d, f in shapes for T in (16, 32)]:
+        cfg = sp.Config(d_model=d, d_ff=f, n_experts=8, top_k=2, weight_dtype=sp.BF16, max_tokens=T)
         for proj, (k_len, n_units) in enumerate([(d // 32, f // 16), (f // 32, d // 32)]):
             p = sp.gemm_plan(cfg, proj)
             waves = p["k_waves"] * p["n_sub"]
             assert 1 <= waves <= 16 and (p["k_steps"] <= 14 or waves <= 8), (d, f, proj, p)
+            if T > 16:
+                # batches of more than 16 tokens: the instances that take 32 tokens of an expert in one weight pass
+                # have at most 8 waves, one N sub-tile, and no more k-steps per wave than their registers hold
+                assert waves <= 8 and p["n_sub"] == 1, (d, f, proj, p)
+                assert not p["exact"] or p["k_steps"] <= (24 if proj == 0 else 16), (d, f, proj, p)
             assert n_units % p["n_sub"] == 0, (d, f, proj, p)
             assert p["lds_bytes"] <= 160 * 1024 // 2, (d, f, proj, p)     # two workgroups per CU still fit its 160 KB
             if proj == 0:
@@ -154,10 +159,14 @@ def test_gemm_plans_fit_what_the_kernels_assume(sp):
                 per = -(-k_len // p["splits"])
                 assert p["k_steps"] == 32 and p["k_waves"] <= 8 and p["k_waves"] * 32 >= per, (d, f, proj, p)
     # the benchmark shapes use the plans the measurements were made with
-    c2 = sp.Config(d_model=4096, d_ff=14336, n_experts=8, top_k=2, weight_dtype=sp.BF16)
+    c2 = sp.Config(d_model=4096, d_ff=14336, n_experts=8, top_k=2, weight_dtype=sp.BF16, max_tokens=8)
     assert (sp.gemm_plan(c2, 0)["k_waves"], sp.gemm_plan(c2, 0)["k_steps"]) == (16, 8)
     p = sp.gemm_plan(c2, 1)
     assert (p["splits"], p["k_waves"], p["k_steps"]) == (2, 16, 14)
+    c5 = sp.Config(d_model=6144, d_ff=16384, n_experts=8, top_k=2, weight_dtype=sp.BF16, max_tokens=32)
+    assert (sp.gemm_plan(c5, 0)["k_waves"], sp.gemm_plan(c5, 0)["k_steps"]) == (8, 24)
+    p = sp.gemm_plan(c5, 1)
+    assert (p["splits"], p["k_waves"], p["k_steps"]) == (4, 8, 16)
     with pytest.raises(sp.SpmoeError):
         sp.gemm_plan(sp.Config(d_model=512, d_ff=1024, n_experts=8, top_k=2, weight_dtype=sp.F32), 0)
     with pytest.raises(sp.SpmoeError):

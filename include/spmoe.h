@@ -263,9 +263,11 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* ctx, int layer, int expert,
  * expert; larger batches use instances of at most 8 waves that take up to 32 tokens of an expert in one pass
  * over its weights (first tile in registers, second tile re-read from the L2 cache k-step by k-step).
  * host_plan_out[0] = K-splits across workgroups, [1] = waves that split the K range of one N sub-tile,
- * [2] = k-steps (of 32 elements) per wave, [3] = N sub-tiles side by side in a workgroup, [4] = 1 if
- * [0] * [1] * [2] covers the contraction exactly, 0 for the generic instance (zero operands past the end),
- * [5] = dynamic LDS bytes of the launch.  Pure host arithmetic; SPMOE_EINVAL for a configuration
+ * [2] = k-steps (of 32 elements) per wave, [3] = N sub-tiles side by side in a workgroup, [4] = flags: bit 0
+ * set if [0] * [1] * [2] covers the contraction exactly (clear: the generic instance, zero operands past the
+ * end), bit 1 set if this projection takes up to 32 tokens of an expert per pass over its weights (clear: 16
+ * per pass, so an expert with more tokens streams its weights twice in this projection; only batches of more
+ * than 16 tokens can meet that case), [5] = dynamic LDS bytes of the launch.  Pure host arithmetic; SPMOE_EINVAL for a configuration
  * spmoe_create would refuse or for fp32 weights (which do not use these kernels). */
 spmoe_status spmoe_gemm_plan(const spmoe_config* cfg, int projection, int32_t host_plan_out[6]);
 

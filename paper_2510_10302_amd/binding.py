@@ -154,12 +154,13 @@ def suggest_cutoff(n_layers, n_layers_draft, k, t_comp, t_io, m_peak, m_expert, 
 
 
 def gemm_plan(cfg, projection):
-    """Tiling of the gate/up (0) or down (1) expert GEMM: dict(splits, k_waves, k_steps, n_sub, exact, lds_bytes)."""
+    """Tiling of the gate/up (0) or down (1) expert GEMM: dict(splits, k_waves, k_steps, n_sub, exact, tokens_per_pass, lds_bytes)."""
     out = (ctypes.c_int32 * 6)()
     st = load_library().spmoe_gemm_plan(ctypes.byref(cfg), projection, ctypes.addressof(out))
     if st != 0:
         raise SpmoeError(st, "spmoe_gemm_plan")
-    return dict(splits=out[0], k_waves=out[1], k_steps=out[2], n_sub=out[3], exact=bool(out[4]), lds_bytes=out[5])
+    return dict(splits=out[0], k_waves=out[1], k_steps=out[2], n_sub=out[3], exact=bool(out[4] & 1),
+                tokens_per_pass=32 if out[4] & 2 else 16, lds_bytes=out[5])
 
 
 def moe_layer_resident_static(cfg, dev_gate, dev_blobs, dev_x, dev_out, stream=None):

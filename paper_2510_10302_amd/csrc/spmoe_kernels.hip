@@ -840,6 +840,7 @@ hipError_t spmoe_launch_permute(hipStream_t stream, const int32_t* idx, int T, i
 struct GemmPlan {
     int splits, kw, ksw, nw;
     bool exact;
+    int ntok = 1;     // token tiles of an expert taken per pass over its weights: 1 (16 tokens) or 2 (32 tokens)
     int waves() const { return kw * nw; }
 };
 
@@ -867,27 +868,32 @@ static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char*
         int s = 0, kw = 0, ksw = 0, nw = 0;
         if (sscanf(force, "%d,%d,%d,%d", &s, &kw, &ksw, &nw) == 4 && s >= 1 && s <= max_splits && nw >= 1 &&
             s * kw * ksw == ks_total && n_units % nw == 0 && is_exact_ksw(ksw) && plan_ok(kw * nw, ksw) &&
-            (!two_tiles || (kw <= 8 && nw == 1 && ksw <= two_tile_max_ksw(mode))))
-            return GemmPlan{s, kw, ksw, nw, true};
+            (!two_tiles || (kw <= 8 && nw == 1 && ksw <= two_tile_max_ksw(mode)))) {
+            GemmPlan fp{s, kw, ksw, nw, true};
+            fp.ntok = two_tiles ? 2 : 1;
+            return fp;
+        }
     }
     if (two_tiles) {
-        // 8 waves first (most bytes in flight), fewest K-splits, then anything exact with at least 4 waves
-        static const int kKswTwo[] = {16, 24, 12, 14, 8, 28, 32, 11, 10, 4};
-        for (int min_kw : {8, 4, 1}) {
-            for (int splits = 1; splits <= max_splits; splits *= 2) {
+        // 8 waves first (most bytes in flight), then anything exact with at least 4 waves; never more K-splits than
+        // the one-tile plan of the shape uses (shorter units pay the per-unit barrier more often: measured 7 % on the
+        // down projection at d = 6144, f = 16384).  Shapes without such a plan keep the one-tile plan, and an expert
+        // with more than 16 tokens then streams its weights once per tile in that projection.
+        const GemmPlan one = plan_gemm(ks_total, n_units, max_splits, env, false, mode);
+        static const int kKswTwo[] = {16, 24, 12, 14, 8, 11, 10, 4};
+        for (int min_kw : {8, 4}) {
+            for (int splits = 1; splits <= one.splits; splits *= 2) {
                 if (ks_total % splits) break;
                 const int per = ks_total / splits;
                 for (int ksw : kKswTwo) {
                     if (per % ksw || ksw > two_tile_max_ksw(mode)) continue;
                     const int kw = per / ksw;
-                    if (kw >= min_kw && kw <= 8) return GemmPlan{splits, kw, ksw, 1, true};
+                    if (kw >= min_kw && kw <= 8) { GemmPlan tp{splits, kw, ksw, 1, true}; tp.ntok = 2; return tp; }
                 }
             }
         }
-        int splits = 1;
-        while ((ks_total + splits - 1) / splits > 8 * 32) ++splits;
-        const int per = (ks_total + splits - 1) / splits;
-        return GemmPlan{splits, (per + 31) / 32, 32, 1, false};
+        if (!one.exact && one.waves() <= 8) { GemmPlan tp = one; tp.ntok = 2; return tp; }   // the generic instance has a two-tile form
+        return one;
     }
     // preference (measured, the differences are small): as few K-splits as possible, one N sub-tile, 9..16 waves
     static const int kKswPreference[] = {12, 8, 11, 14, 16, 4, 10, 24, 28, 32};
@@ -941,8 +947,8 @@ static size_t gemm_lds_bytes(int waves, int ntok) {
 
 void spmoe_describe_plan(int projection, int d, int f, int T, int32_t out[6]) {
     const GemmPlan p = projection == 0 ? plan_gate_up(d, f, T > 16) : plan_down(d, f, T > 16);
-    out[0] = p.splits; out[1] = p.kw; out[2] = p.ksw; out[3] = p.nw; out[4] = p.exact ? 1 : 0;
-    out[5] = (int32_t)gemm_lds_bytes(p.waves(), T > 16 ? 2 : 1);
+    out[0] = p.splits; out[1] = p.kw; out[2] = p.ksw; out[3] = p.nw; out[4] = (p.exact ? 1 : 0) | (p.ntok == 2 ? 2 : 0);
+    out[5] = (int32_t)gemm_lds_bytes(p.waves(), p.ntok);
 }
 
 // Persistent grid size: as many workgroups as fit on the chip at once for this instance.
@@ -1028,8 +1034,9 @@ hipError_t spmoe_launch_gate_up(hipStream_t stream, int dtype, const SpmoeShape&
     p.x = x;
     p.h = static_cast<uint16_t*>(h);
     if (dtype == SPMOE_BF16) {
-        const bool two = s.T > 16;        // more than 16 tokens: an expert may get up to 32, taken in one pass
-        const GemmPlan plan = plan_gate_up(s.d, s.f, two);
+        // more than 16 tokens: an expert may get up to 32, taken in one pass where the shape has a plan for it
+        const GemmPlan plan = plan_gate_up(s.d, s.f, s.T > 16);
+        const bool two = plan.ntok == 2;
         p.ks_total = s.d / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;
         p.splits = plan.splits;
@@ -1050,8 +1057,8 @@ hipError_t spmoe_launch_down(hipStream_t stream, int dtype, const SpmoeShape& s,
     p.h = static_cast<uint16_t*>(const_cast<void*>(h));
     p.ypart = ypart;
     if (dtype == SPMOE_BF16) {
-        const bool two = s.T > 16;
-        const GemmPlan plan = plan_down(s.d, s.f, two);
+        const GemmPlan plan = plan_down(s.d, s.f, s.T > 16);
+        const bool two = plan.ntok == 2;
         if (plan.splits != splits) return hipErrorInvalidValue;
         p.ks_total = s.f / 32;
         p.ks_split = (p.ks_total + plan.splits - 1) / plan.splits;

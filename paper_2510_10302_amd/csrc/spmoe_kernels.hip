@@ -146,7 +146,7 @@ __device__ void group_assignments(const int32_t* idx, int T, int k, int E, int n
 }
 
 // ---------------------------------------------------------------------------------------------
-// K1: gate logits + softmax + top-k.  Grid = T, block = 256 (512 for E >= 32).  The token-to-expert grouping
+// K1: gate logits + softmax + top-k.  Grid = T, block = 4 or 8 waves.  The token-to-expert grouping
 // is not done here: every workgroup of the expert GEMMs derives it from idx in LDS (a few hundred integers),
 // which costs less than a second pass over all tokens behind a device-wide arrival counter would.
 // ---------------------------------------------------------------------------------------------
@@ -229,8 +229,8 @@ __device__ __forceinline__ void gate_logits_pass(const float* __restrict__ xt, c
     }
 }
 
-template <typename WT>
-__global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict__ x, const WT* __restrict__ wg,
+template <typename WT, int EPW, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gate_topk_kernel(const float* __restrict__ x, const WT* __restrict__ wg,
                                                         int T, int E, int d, int k, int renorm,
                                                         int32_t* __restrict__ idx_out, float* __restrict__ w_out,
                                                         float* __restrict__ logits_out, int32_t* steal,
@@ -243,13 +243,10 @@ __global__ __launch_bounds__(512) void gate_topk_kernel(const float* __restrict_
     // the unit counters of the two expert GEMMs that follow start at zero
     if (steal != nullptr && t == 0 && tid < 2) steal[tid] = 0;
 
-    // ---- gate logits: each wave scores `epw` experts per pass; all loads of a round (KI chunks of 8
+    // ---- gate logits: each wave scores EPW experts per pass; all loads of a round (KI chunks of 8
     //      elements per lane, for every expert of the pass) are issued before the arithmetic starts
-    const int epw = (E >= 16) ? 4 : (E >= 8 ? 2 : 1);
     uint16_t* xb_row = (xb_out != nullptr && wave == 0) ? xb_out + (size_t)t * d : nullptr;
-    if (epw == 4) gate_logits_pass<WT, 4>(xt, wg, E, d, wave, lane, s_logit, xb_row);
-    else if (epw == 2) gate_logits_pass<WT, 2>(xt, wg, E, d, wave, lane, s_logit, xb_row);
-    else gate_logits_pass<WT, 1>(xt, wg, E, d, wave, lane, s_logit, xb_row);
+    gate_logits_pass<WT, EPW>(xt, wg, E, d, wave, lane, s_logit, xb_row);
     __syncthreads();
     if (wave != 0) return;
 
@@ -818,15 +815,41 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
+// Experts per wave and pass (EPW) and waves per workgroup are chosen so that, where the shape allows, a lane has
+// all its loads of the token in flight at once (one round: 16 / EPW chunks of 8 bf16 weights per lane and expert,
+// 8 / EPW for fp32) and every expert is scored in one pass.  The choice depends on E and d only, so a token's
+// logits do not depend on the batch it arrives in.
+template <typename WT, int EPW>
+static void launch_gate_topk_waves(hipStream_t stream, int waves, const float* x, const WT* wg, int T, int E, int d, int k,
+                                   int renorm, int32_t* idx, float* w, float* logits, int32_t* steal, uint16_t* xb) {
+    if (waves <= 4)
+        hipLaunchKernelGGL((gate_topk_kernel<WT, EPW, 4>), dim3(T), dim3(256), 0, stream, x, wg, T, E, d, k, renorm, idx, w,
+                           logits, steal, xb);
+    else   // more experts than 8 waves score in one pass take further passes (16 waves would leave 128 registers: spills)
+        hipLaunchKernelGGL((gate_topk_kernel<WT, EPW, 8>), dim3(T), dim3(512), 0, stream, x, wg, T, E, d, k, renorm, idx, w,
+                           logits, steal, xb);
+}
+
+template <typename WT>
+static void launch_gate_topk_typed(hipStream_t stream, const float* x, const WT* wg, int T, int E, int d, int k, int renorm,
+                                   int32_t* idx, float* w, float* logits, int32_t* steal, uint16_t* xb) {
+    const int chunks = (d / 8 + 63) / 64;                       // 8-element chunks per lane
+    const int ki_max = sizeof(WT) == 2 ? 16 : 8;
+    const int epw = (ki_max / 4 >= chunks) ? 4 : ((ki_max / 2 >= chunks) ? 2 : 1);
+    const int waves = (E + epw - 1) / epw;
+    if (epw == 4) launch_gate_topk_waves<WT, 4>(stream, waves, x, wg, T, E, d, k, renorm, idx, w, logits, steal, xb);
+    else if (epw == 2) launch_gate_topk_waves<WT, 2>(stream, waves, x, wg, T, E, d, k, renorm, idx, w, logits, steal, xb);
+    else launch_gate_topk_waves<WT, 1>(stream, waves, x, wg, T, E, d, k, renorm, idx, w, logits, steal, xb);
+}
+
 hipError_t spmoe_launch_gate_topk(hipStream_t stream, int dtype, const float* x, const void* wg, int T, int E, int d,
                                   int k, int renorm, int32_t* idx, float* w, float* logits, int32_t* steal, void* xb) {
-    const int threads = (E >= 32) ? 512 : 256;
     if (dtype == SPMOE_BF16)
-        hipLaunchKernelGGL(gate_topk_kernel<uint16_t>, dim3(T), dim3(threads), 0, stream, x, static_cast<const uint16_t*>(wg),
-                           T, E, d, k, renorm, idx, w, logits, steal, static_cast<uint16_t*>(xb));
+        launch_gate_topk_typed<uint16_t>(stream, x, static_cast<const uint16_t*>(wg), T, E, d, k, renorm, idx, w, logits,
+                                         steal, static_cast<uint16_t*>(xb));
     else
-        hipLaunchKernelGGL(gate_topk_kernel<float>, dim3(T), dim3(threads), 0, stream, x, static_cast<const float*>(wg), T, E,
-                           d, k, renorm, idx, w, logits, steal, static_cast<uint16_t*>(nullptr));
+        launch_gate_topk_typed<float>(stream, x, static_cast<const float*>(wg), T, E, d, k, renorm, idx, w, logits, steal,
+                                      nullptr);
     return hipGetLastError();
 }
 
@@ -895,7 +918,14 @@ static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char*
         if (!one.exact && one.waves() <= 8) { GemmPlan tp = one; tp.ntok = 2; return tp; }   // the generic instance has a two-tile form
         return one;
     }
-    // preference (measured, the differences are small): as few K-splits as possible, one N sub-tile, 9..16 waves
+    // gate/up: 8 waves of at most 16 k-steps where the contraction divides that way.  Measured against the 16-wave
+    // plans: 3 % faster at d = 4096 (8 x 16, with the dynamic tail of the unit schedule, which 8-wave launches use),
+    // 2 % at d = 2048 (8 x 8, two workgroups per CU); 8 x 24 at d = 6144 is 0.5 % slower than 16 x 12 and is not taken.
+    if (mode == MODE_GU) {
+        for (int ksw : {16, 8, 12, 14})
+            if (ks_total == 8 * ksw) return GemmPlan{1, 8, ksw, 1, true};
+    }
+    // otherwise (measured, the differences are small): as few K-splits as possible, one N sub-tile, 9..16 waves
     static const int kKswPreference[] = {12, 8, 11, 14, 16, 4, 10, 24, 28, 32};
     for (int splits = 1; splits <= max_splits; splits *= 2) {
         if (ks_total % splits) break;

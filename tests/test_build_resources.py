@@ -26,3 +26,5 @@ def test_expert_gemm_instances_use_no_scratch_memory():
     gemms = {n: v for n, v in seen.items() if "expert_gemm_kernel" in n}
     assert len(gemms) >= 20, sorted(seen)
     assert all(v == 0 for v in gemms.values()), {n: v for n, v in gemms.items() if v}
+    routing = {n: v for n, v in seen.items() if "gate_topk_kernel" in n}
+    assert len(routing) >= 12 and all(v == 0 for v in routing.values()), routing

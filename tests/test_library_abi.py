@@ -160,7 +160,7 @@ def test_gemm_plans_fit_what_the_kernels_assume(sp):
                 assert p["k_steps"] == 32 and p["k_waves"] <= 8 and p["k_waves"] * 32 >= per, (d, f, proj, p)
     # the benchmark shapes use the plans the measurements were made with
     c2 = sp.Config(d_model=4096, d_ff=14336, n_experts=8, top_k=2, weight_dtype=sp.BF16, max_tokens=8)
-    assert (sp.gemm_plan(c2, 0)["k_waves"], sp.gemm_plan(c2, 0)["k_steps"]) == (16, 8)
+    assert (sp.gemm_plan(c2, 0)["k_waves"], sp.gemm_plan(c2, 0)["k_steps"]) == (8, 16)
     p = sp.gemm_plan(c2, 1)
     assert (p["splits"], p["k_waves"], p["k_steps"]) == (2, 16, 14)
     c5 = sp.Config(d_model=6144, d_ff=16384, n_experts=8, top_k=2, weight_dtype=sp.BF16, max_tokens=32)

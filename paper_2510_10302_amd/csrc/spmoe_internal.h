@@ -11,7 +11,7 @@
 
 // Byte offsets inside one packed expert blob.
 //   bf16: [GU region: (f/16) N-tiles x (d/32) k-steps x {gate tile, up tile} x 1 KiB]
-//         [D  region: (d/16) N-tiles x (f/32) k-steps x 1 KiB]
+//         [D  region: (d/32) N-tile pairs x (f/32) k-steps x {tile of N-tile 2p, tile of N-tile 2p+1} x 1 KiB]
 //         one 1 KiB tile = 64 lanes x 8 bf16; lane l holds row (l & 15), K elements 8*(l >> 4) .. +7
 //         of the 16 x 32 block, i.e. exactly the A operand of v_mfma_f32_16x16x32_bf16.
 //   fp32: W_gate[f][d], W_up[f][d], W_down[d][f] back to back, row-major.

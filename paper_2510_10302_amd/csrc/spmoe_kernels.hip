@@ -384,12 +384,12 @@ constexpr int ring_depth(int ksw, int limit) {
 template <int MODE, int KSW, bool EXACT, int NTOK>
 __global__ __launch_bounds__(((KSW > 14 || NTOK == 2) ? 8 : 16) * 64) void expert_gemm_kernel(const SpmoeExpertList list,
                                                                                                const GemmParams p) {
-    // Two weight tiles are in flight per k-step: gate and up tile of one N-tile (adjacent KiB) in MODE_GU,
-    // the tiles of two consecutive N-tiles in MODE_DOWN (ks_total KiB apart); both share the B operand.
+    // Two weight tiles are in flight per k-step, adjacent KiB of the blob that share the B operand: gate and up
+    // tile of one N-tile in MODE_GU, the tiles of two consecutive N-tiles in MODE_DOWN.
     constexpr int NMAT = 2;
     constexpr int PF = ring_depth(KSW, 4);
-    constexpr int STEP = (MODE == MODE_GU) ? 128 : 64;    // 16-byte units between consecutive k-steps of a stream
-    const size_t soff = (MODE == MODE_GU) ? 64 : (size_t)p.ks_total * 64;   // second stream's offset
+    constexpr int STEP = 128;                             // 16-byte units between consecutive k-steps of a stream
+    constexpr size_t soff = 64;                           // second tile of the k-step
     extern __shared__ float s_mem[];
     float* s_red = s_mem;                                 // [2][waves][NMAT][NTOK][64 lanes][4]
     const void** s_blob = reinterpret_cast<const void**>(s_mem + 2 * p.waves * NMAT * NTOK * 256);   // [SPMOE_MAX_ETOT] copy of list.blob
@@ -511,9 +511,8 @@ __global__ __launch_bounds__(((KSW > 14 || NTOK == 2) ? 8 : 16) * 64) void exper
         const int ks_hi = min(min(ks_lo + KSW, (s + 1) * p.ks_split), p.ks_total);
         nks = EXACT ? KSW : max(ks_hi - ks_lo, 0);
         const char* blob = static_cast<const char*>(s_blob[li]) + region;
-        const size_t sub = (size_t)nt * p.nw + nsub;                                   // this wave's sub-tile
-        const size_t tile = (MODE == MODE_GU) ? sub : 2 * sub;                        // its first weight tile
-        return reinterpret_cast<const bf16x8*>(blob) + (tile * p.ks_total + ks_lo) * STEP + lane;
+        const size_t sub = (size_t)nt * p.nw + nsub;                                   // this wave's sub-tile (pair of tiles)
+        return reinterpret_cast<const bf16x8*>(blob) + (sub * p.ks_total + ks_lo) * STEP + lane;
     };
 
     int nks = KSW;

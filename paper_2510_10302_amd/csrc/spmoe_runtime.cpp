@@ -528,7 +528,7 @@ spmoe_status spmoe_pack_expert(const spmoe_config* cfg, const void* host_w_gate,
             }
         }
     }
-    {   // down: rows i in [0,d), contraction over f
+    {   // down: rows i in [0,d), contraction over f; the tiles of N-tiles 2p and 2p+1 interleaved per k-step
         Chunk* od = out + (2 * d * f) / 8;
         const size_t ks_total = f / 32, chunks_per_row = f / 8;
         #pragma omp parallel for schedule(static)
@@ -536,7 +536,7 @@ spmoe_status spmoe_pack_expert(const spmoe_config* cfg, const void* host_w_gate,
             const size_t nt = i / 16, r = i % 16;
             for (size_t cidx = 0; cidx < chunks_per_row; ++cidx) {
                 const size_t ks = cidx / 4, kg = cidx % 4, lane = kg * 16 + r;
-                od[(nt * ks_total + ks) * 64 + lane] = dn[i * chunks_per_row + cidx];
+                od[(((nt / 2) * ks_total + ks) * 2 + (nt % 2)) * 64 + lane] = dn[i * chunks_per_row + cidx];
             }
         }
     }

@@ -157,7 +157,7 @@ def run_resident(name, spec, args, steps, warmup, keep_for_cpu=False):
 
     # latency distribution: each call between its own pair of HIP events on the compute stream (separate pass; the
     # events sit between the layers, not inside them)
-    n_lat = min(steps, 200)
+    n_lat = 200
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_lat)]
     for i, (a, b) in enumerate(evs):
         a.record(stream)
@@ -171,7 +171,7 @@ def run_resident(name, spec, args, steps, warmup, keep_for_cpu=False):
     # per-kernel durations from HIP events on the compute stream (separate pass: the events sit between kernels)
     kms = np.zeros(4)
     bytes_gu = bytes_dn = 0.0
-    n_prof = min(steps, 5 * len(xs))
+    n_prof = 3 * len(xs)
     for i in range(n_prof):
         ctx.profile_begin()
         step(i)

@@ -238,6 +238,23 @@ def cpu_baseline(wl, xs_host, T, k, seconds=10.0):
                       "FFN rows" % (T, len(xs_host), seconds, legs["single_thread"]["batches"], best["batches"], threads)}
 
 
+def cpu_stack_estimate(wl, xs_host, T, k, stack_layers, evals=4):
+    """CPU oracle time of a whole stack of this layer shape: `evals` layer evaluations timed (OpenMP, all host
+    threads), scaled linearly to the stack's layer count."""
+    import oracle
+    orc = oracle.Oracle("f32")
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    t1 = time.perf_counter()
+    for n in range(evals):
+        orc.moe_layer(xs_host[n % len(xs_host)], wl.gate[0], wl.layer_experts(0), k, shared=wl.shared[0])
+    per_layer = (time.perf_counter() - t1) / evals
+    return {"kind": "oracle", "threads": threads, "ms_per_layer": per_layer * 1e3, "layers_timed": evals,
+            "stack_layers": stack_layers, "stack_ms_scaled": per_layer * 1e3 * stack_layers,
+            "stack_tokens_per_s_scaled": T / (per_layer * stack_layers),
+            "sample": "%d evaluations of one layer of this shape (fp32 C oracle, OpenMP over FFN rows), scaled linearly to the "
+                      "%d layers of the stack" % (evals, stack_layers)}
+
+
 # ---------------------------------------------------------------------------------------------------------------
 # offloaded stack
 # ---------------------------------------------------------------------------------------------------------------
@@ -484,14 +501,24 @@ def main():
         result[key] = block[key]
     if keep is not None:
         result["cpu_baseline"] = cpu_baseline(keep[0], keep[1], spec["T"], spec["k"])
+        if composite:
+            # configuration 3 is a 32-layer stack of this layer shape
+            result["cpu_baseline"]["stack_c3_mixtral_8x7b"] = {
+                "stack_layers": 32, "stack_ms_scaled": result["cpu_baseline"]["ms_per_step"] * 32,
+                "stack_tokens_per_s_scaled": spec["T"] / (result["cpu_baseline"]["ms_per_step"] * 1e-3 * 32),
+                "sample": "the OpenMP per-layer time above scaled linearly to the 32 layers of the stack"}
         keep = None
     if composite and not args.no_extras:
         # the other single-GPU layer shapes (the Mixtral-8x22B layer is the largest configuration), shorter runs
         result["layers"] = {}
         for other in ("c4_deepseek_v2_lite", "c5_mixtral_8x22b"):
             ospec = dict(W.CONFIGS[other])
-            oblock, _ = run_resident(other, ospec, args, max(100, args.steps // 2), args.warmup)
+            oblock, okeep = run_resident(other, ospec, args, max(100, args.steps // 2), args.warmup,
+                                         keep_for_cpu=not args.no_cpu_baseline)
             oblock.pop("dtype")
+            if okeep is not None:
+                oblock["cpu_baseline_stack"] = cpu_stack_estimate(okeep[0], okeep[1], ospec["T"], ospec["k"], ospec["layers"])
+                okeep = None
             result["layers"][other] = oblock
         # the third part of the metric: one offloaded stack at the cutoff the policy admits
         oargs = argparse.Namespace(**vars(args))

@@ -215,7 +215,7 @@ spmoe_status spmoe_prefetch_drain(spmoe_ctx* ctx);
  * loaded on demand (evicting the LRU head) and computed as their copies land.  When every routed
  * expert of the layer is resident the call is fully asynchronous: the host never learns the routing,
  * so that call neither counts hits nor changes the LRU order (nothing can be evicted then anyway).
- * Otherwise it waits for the per-expert token counts to reach the host before it returns.  The result
+ * Otherwise it waits for the routing result (T * top_k expert ids) to reach the host before it returns.  The result
  * does not depend on the cache state. */
 spmoe_status spmoe_moe_verify_layer(spmoe_ctx* ctx, int layer, const float* dev_x, int T, float* dev_out);
 

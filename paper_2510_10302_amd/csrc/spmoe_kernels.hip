@@ -1,18 +1,21 @@
 // HIP kernels of the SP-MoE verify-layer hot path for gfx950 (CDNA4, wave64).
 //
 //   gate_topk_kernel     gate logits + softmax + top-k + gating scores (Eq. 1's G(x); Alg. 1's
-//                        Gates[l](s) and TopK_Index), one workgroup per token; the last workgroup to
-//                        finish groups the assignments by expert (counts / offsets / perm).
+//                        Gates[l](s) and TopK_Index), one workgroup per token; also leaves the batch
+//                        rounded to bf16 for the expert path.
 //   expert_gemm_kernel   the grouped SwiGLU expert FFN (Eq. 1's E_i(x)) as two skinny GEMMs whose A
-//                        operand is the streamed weight tile and whose B operand is the (<= 16) token
-//                        tile held in registers; bf16 x bf16 -> fp32 on v_mfma_f32_16x16x32_bf16.
+//                        operand is the streamed weight tile and whose B operand is the token tile
+//                        (16 tokens held in registers; a second 16 re-read from L2 in the instances for
+//                        batches of more than 16 tokens); bf16 x bf16 -> fp32 on v_mfma_f32_16x16x32_bf16.
+//                        Its prologue groups the assignments by expert in LDS.
 //   expert_gemm_f32_kernel  the same contraction for fp32 weights on the vector ALU.
 //   combine_kernel       out[t] = sum_r w[t][r] * y[t][r] (+ shared experts), fixed summation order.
 //
 // The expert GEMMs are bound by streaming each active expert's weights from HBM exactly once: with a
 // handful of tokens per expert every weight byte feeds one MFMA.  Weights are therefore stored
 // pre-tiled (see spmoe_internal.h) so that one wave-wide 16-byte-per-lane load is a contiguous 1 KiB
-// line group that is already in MFMA A-operand order; no LDS staging of weights is needed.
+// line group that is already in MFMA A-operand order, and the two tiles of a k-step are adjacent; no LDS
+// staging of weights is needed.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>

@@ -27,6 +27,22 @@ misses and evictions that the library must report.
 """
 
 
+def rank_predicted(pidx, prob, n_experts):
+    """Alg. 1's `experts` when one task scores several draft states at once (the paper's hook fires per draft
+    token, so it is silent here; with one state this is TopK_Index's own order): every expert some state selected,
+    most-voted first, then larger summed gate probability over the states that selected it, then lower index.
+    pidx[n][k]: selected experts per state; prob[n][E]: softmax probabilities per state."""
+    votes = [0] * n_experts
+    psum = [0.0] * n_experts
+    for t, row in enumerate(pidx):
+        for e in row:
+            e = int(e)
+            votes[e] += 1
+            psum[e] += float(prob[t][e])
+    chosen = [e for e in range(n_experts) if votes[e] > 0]
+    return sorted(chosen, key=lambda e: (-votes[e], -psum[e], e))
+
+
 class CacheModel:
     def __init__(self, n_layers, n_experts, slots, cutoff_layer=-1):
         self.n_layers, self.n_experts, self.slots, self.cutoff = n_layers, n_experts, slots, cutoff_layer

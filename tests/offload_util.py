@@ -5,6 +5,7 @@ beside every call."""
 import numpy as np
 
 import spmoe_inputs as si
+from oracle.cache_model import rank_predicted
 from parity_util import NEAR_TIE, REL_L2_BF16, check_layer, gpu_layer, oracle_layer
 
 STAT_KEYS = ("hits", "misses", "evictions", "prefetch_issued", "prefetch_used", "prefetch_wasted", "ondemand_loads")
@@ -15,17 +16,12 @@ def ranked_prediction(oracle, draft, gate, pred_k, E):
     most-voted first, then larger summed probability, then lower index.  Returns (ranking, smallest logit gap that
     decided a selection)."""
     pidx, plog, pp = oracle.predict_experts(draft, gate, pred_k)
-    votes = np.bincount(pidx.reshape(-1), minlength=E)
-    psum = np.zeros(E)
     gap = np.inf
     for t in range(draft.shape[0]):
-        for e in pidx[t]:
-            psum[e] += pp[t, e]
         top = np.sort(np.asarray(plog[t], np.float64))[::-1][: pred_k + 1]
         if top.size > 1:
             gap = min(gap, float((-np.diff(top)).min()))
-    ranked = sorted([e for e in range(E) if votes[e]], key=lambda e: (-votes[e], -psum[e], e))
-    return ranked, gap
+    return rank_predicted(pidx, pp, E), gap
 
 
 def run_offloaded_stack(L, wl, model, oracle, layers, T, sigma, pred_k, seed, iterations, mode,

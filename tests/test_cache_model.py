@@ -118,6 +118,24 @@ def test_a_task_keeps_the_cached_experts_it_predicted():
             assert set(ranked[:S]) <= set(m.contents(0)), (trial, step, ranked, m.contents(0))
 
 
+def test_ranking_of_a_prediction_over_several_draft_states():
+    _check_ranking(cache_model)
+
+
+def _check_ranking(cache_model):
+    # hand-worked: three draft states, top-2 each, six experts
+    #   state 0 selects 2 (p 0.50) and 5 (p 0.30); state 1 selects 2 (0.40) and 1 (0.35); state 2 selects 5 (0.45) and 1 (0.20)
+    #   votes 2 / 2 / 2 for experts 2, 5, 1; summed probabilities 0.90 / 0.75 / 0.55 -> 2, 5, 1
+    prob = [[0, 0.10, 0.50, 0.05, 0.05, 0.30], [0.05, 0.35, 0.40, 0.10, 0.05, 0.05], [0.10, 0.20, 0.05, 0.10, 0.10, 0.45]]
+    assert cache_model.rank_predicted([[2, 5], [2, 1], [5, 1]], prob, 6) == [2, 5, 1]
+    # votes come before probability: expert 0 is named twice with little mass, expert 3 once with a lot
+    prob = [[0.10, 0.05, 0.05, 0.80], [0.15, 0.60, 0.20, 0.05]]
+    assert cache_model.rank_predicted([[3, 0], [1, 0]], prob, 4) == [0, 3, 1]
+    # equal votes and equal mass: the lower index first; one state: TopK_Index's own order survives
+    assert cache_model.rank_predicted([[3, 2]], [[0.1, 0.1, 0.4, 0.4]], 4) == [2, 3]
+    assert cache_model.rank_predicted([[1, 3]], [[0.05, 0.6, 0.05, 0.3]], 4) == [1, 3]
+
+
 def test_filter_cached_matches_alg1():
     m = CacheModel(1, 8, 3, cutoff_layer=0)
     m.prefetch(0, [4, 5])
@@ -179,6 +197,10 @@ MUTANTS = {
     "prefetch_not_cut": ("        uniq = uniq[: self.slots]\n", ""),
     "ondemand_not_counted": ('            self.stats["ondemand_loads"] += 1', "            pass"),
     "issued_not_counted": ('            self.stats["prefetch_issued"] += 1', "            pass"),
+    "ranking_ignores_votes": ("    return sorted(chosen, key=lambda e: (-votes[e], -psum[e], e))",
+                              "    return sorted(chosen, key=lambda e: (-psum[e], e))"),
+    "ranking_ties_to_higher_index": ("    return sorted(chosen, key=lambda e: (-votes[e], -psum[e], e))",
+                                     "    return sorted(chosen, key=lambda e: (-votes[e], -psum[e], -e))"),
     "misses_loaded_before_hits_touched": ("""        for e in hits:
             self._touch(layer, e)
             if e in self.unused_prefetch[layer]:
@@ -213,4 +235,8 @@ def test_planted_mistake_in_the_cache_model_is_caught(name):
         spec = importlib.util.spec_from_file_location("mutant_%s" % name, path)
         mod = importlib.util.module_from_spec(spec)
         spec.loader.exec_module(mod)
+        if name.startswith("ranking"):
+            with pytest.raises(AssertionError):
+                _check_ranking(mod)
+            return
         assert trace_failures(mod.CacheModel), "the traces did not notice the planted mistake '%s'" % name

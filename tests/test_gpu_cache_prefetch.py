@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import spmoe_inputs as si
-from oracle.cache_model import CacheModel
+from oracle.cache_model import CacheModel, rank_predicted
 from parity_util import REL_L2_BF16, gpu_layer, oracle_layer, rel_l2
 
 pytestmark = pytest.mark.gpu
@@ -50,13 +50,7 @@ def test_bookkeeping_matches_cache_model(oracle32):
             # ... and on the reference: top-pred_k per draft token, ranked by votes / probability / index
             if layer <= cutoff:
                 pidx, plog, pp = oracle32.predict_experts(draft, wl.gate[layer], 2)
-                votes = np.bincount(pidx.reshape(-1), minlength=E)
-                psum = np.zeros(E)
-                for t in range(T):
-                    for e in pidx[t]:
-                        psum[e] += pp[t, e]
-                ranked = sorted([e for e in range(E) if votes[e]], key=lambda e: (-votes[e], -psum[e], e))
-                assert ids == model.filter_cached(layer, ranked)
+                assert ids == model.filter_cached(layer, rank_predicted(pidx, pp, E))
             else:
                 assert ids == []
             L.ctx.prefetch(layer, ids)

@@ -230,8 +230,8 @@ spmoe_status spmoe_moe_verify_layer(spmoe_ctx* ctx, int layer, const float* dev_
  * The intermediates live in one fixed device array of SPMOE_STATIC_SCRATCH_BYTES per GPU, shared by all
  * calls on that GPU: calls that may overlap on one GPU (different streams or threads) race and must be
  * serialised by the caller.  SPMOE_ERANGE if this call needs more than the array holds, roughly
- *   A*f*sizeof(weight) + splits*A*d*4 + 64 KiB,  A = T*(top_k + n_shared), splits <= 4 K-splits of the down GEMM
- * (5.3 MB for d=6144, f=16384, top-2, T=32).  SPMOE_EINVAL for a bad configuration, NULL or misaligned
+ *   A*f*sizeof(weight) + splits*A*d*4 + T*d*2 + 64 KiB,  A = T*(top_k + n_shared), splits <= 4 K-splits of the down GEMM
+ * (5.7 MB for d=6144, f=16384, top-2, T=32).  SPMOE_EINVAL for a bad configuration, NULL or misaligned
  * pointers; SPMOE_EHIP if a launch fails.  Asynchronous on `stream`. */
 #define SPMOE_STATIC_SCRATCH_BYTES (16u << 20)
 spmoe_status spmoe_moe_layer_resident_static(const spmoe_config* cfg, void* stream, const void* dev_gate,

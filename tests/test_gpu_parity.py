@@ -219,6 +219,7 @@ def test_c5_mixtral_8x22b_layer_full_size(oracle32):
     (4096, 14336, 8, 2, 0, 24, 0.9),    # Mixtral-8x7B layer with a 24-token batch
     (512, 1408, 16, 4, 2, 32, 0.97),    # shared experts always see all 32 tokens; ragged contraction (44 k-steps)
     (256, 416, 4, 1, 0, 19, 0.99),      # 19 tokens, top-1: 18 on one expert, two of them in the second tile; generic plan (13 k-steps)
+    (416, 224, 6, 2, 0, 30, 0.98),      # both projections on the generic instance (13 and 7 k-steps), experts with 30 and 18 tokens
 ])
 def test_experts_with_more_than_16_tokens_one_weight_pass(d, f, E, k, shared, T, rho, oracle32):
     # batches of more than 16 tokens use the kernel instances that take up to 32 tokens of an expert in one pass

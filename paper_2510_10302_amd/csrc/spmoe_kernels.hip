@@ -88,6 +88,14 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
     return v;
 }
 
+// 16-byte load from a pointer known to be device memory.  Pointers that reach a kernel inside a struct are generic
+// to the compiler, and loads through them become flat loads, which count against both memory counters (so a wait
+// for LDS also waits for them) and keep their addresses in register pairs.
+__device__ __forceinline__ u32x4 load_global_16(const void* p) {
+    return *reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(
+        (const __attribute__((address_space(1))) void*)p);
+}
+
 // fp32 -> bf16 bits, round to nearest even (finite inputs)
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     uint32_t u = __builtin_bit_cast(uint32_t, f);
@@ -553,7 +561,8 @@ __global__ __launch_bounds__(((KSW > 14 || NTOK == 2) ? 8 : 16) * 64) void exper
     // NTOK = 2 only: the B operand of the group's second token tile (tokens 16..31) does not fit in registers
     // beside the first one; it is re-read for every unit, k-step by k-step, through a small ring of its own.  It
     // is the same KSW KiB per wave for every unit of a group, so these loads hit in the L2 and cost no HBM traffic.
-    bf16x8 ring1[NTOK == 2 ? PF : 1];
+    constexpr int PF1 = (NTOK == 2) ? ((KSW > 28 && PF >= 2) ? 2 : PF) : 1;   // 32 k-steps of first tile leave room for 2
+    bf16x8 ring1[PF1];
     const uint16_t* brow1 = nullptr;                      // this lane's row of the second tile, NULL: no such token
     bool two = false;                                     // the current group has more than 16 tokens
 
@@ -590,7 +599,7 @@ __global__ __launch_bounds__(((KSW > 14 || NTOK == 2) ? 8 : 16) * 64) void exper
 #pragma unroll
             for (int j = 0; j < KSW; ++j) {
                 u32x4 packed = {0u, 0u, 0u, 0u};
-                if (a_n >= 0 && (EXACT || j < nks)) packed = *reinterpret_cast<const u32x4*>(brow + j * 32);
+                if (a_n >= 0 && (EXACT || j < nks)) packed = load_global_16(brow + j * 32);
                 xr[j] = __builtin_bit_cast(bf16x8, packed);
             }
             if (NTOK == 2) {
@@ -598,10 +607,10 @@ __global__ __launch_bounds__(((KSW > 14 || NTOK == 2) ? 8 : 16) * 64) void exper
                 const int a_1 = (two && n < cnt - 16) ? s_perm[beg + 16 + n] : -1;
                 brow1 = (a_1 >= 0) ? bsrc + (size_t)row_of(a_1) * K : nullptr;
 #pragma unroll
-                for (int j = 0; j < PF; ++j) {
+                for (int j = 0; j < PF1; ++j) {
                     u32x4 packed = {0u, 0u, 0u, 0u};
-                    if (brow1 != nullptr && (EXACT || j < nks)) packed = *reinterpret_cast<const u32x4*>(brow1 + j * 32);
-                    ring1[NTOK == 2 ? j : 0] = __builtin_bit_cast(bf16x8, packed);
+                    if (brow1 != nullptr && (EXACT || j < nks)) packed = load_global_16(brow1 + j * 32);
+                    ring1[j] = __builtin_bit_cast(bf16x8, packed);
                 }
             }
         }
@@ -641,11 +650,11 @@ __global__ __launch_bounds__(((KSW > 14 || NTOK == 2) ? 8 : 16) * 64) void exper
                     // second tile: the same weight tiles against tokens 16..31.  Its operand ring refills from the
                     // same rows: later steps of this unit, then the first steps again for the next unit (a change
                     // of group or K-split reloads them above).
-                    const bf16x8 b1 = ring1[NTOK == 2 ? j % PF : 0];
-                    const int jn = (j + PF < KSW) ? j + PF : j + PF - KSW;
+                    const bf16x8 b1 = ring1[j % PF1];
+                    const int jn = (j + PF1 < KSW) ? j + PF1 : j + PF1 - KSW;
                     u32x4 packed = {0u, 0u, 0u, 0u};
-                    if (brow1 != nullptr && (EXACT || jn < nks)) packed = *reinterpret_cast<const u32x4*>(brow1 + jn * 32);
-                    ring1[NTOK == 2 ? j % PF : 0] = __builtin_bit_cast(bf16x8, packed);
+                    if (brow1 != nullptr && (EXACT || jn < nks)) packed = load_global_16(brow1 + jn * 32);
+                    ring1[j % PF1] = __builtin_bit_cast(bf16x8, packed);
 #pragma unroll
                     for (int m = 0; m < NMAT; ++m) acc1[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], b1, acc1[m], 0, 0, 0);
                 }
@@ -885,7 +894,7 @@ static bool plan_ok(int waves, int ksw) { return waves >= 1 && waves <= 16 && (k
 // one pass over its weights (batches of more than 16 tokens): at most 8 waves, one N sub-tile.
 // k-steps per wave the two-tile instances can hold in registers (256 VGPRs at 8 waves per workgroup): the second
 // tile's ring and accumulators come on top of the first tile's KSW * 4 registers.
-constexpr int two_tile_max_ksw(int mode) { return mode == MODE_GU ? 24 : 16; }
+constexpr int two_tile_max_ksw(int mode) { return mode == MODE_GU ? 28 : 32; }
 
 static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char* env, bool two_tiles, int mode) {
     const char* force = getenv(env);
@@ -905,7 +914,7 @@ static GemmPlan plan_gemm(int ks_total, int n_units, int max_splits, const char*
         // down projection at d = 6144, f = 16384).  Shapes without such a plan keep the one-tile plan, and an expert
         // with more than 16 tokens then streams its weights once per tile in that projection.
         const GemmPlan one = plan_gemm(ks_total, n_units, max_splits, env, false, mode);
-        static const int kKswTwo[] = {16, 24, 12, 14, 8, 11, 10, 4};
+        static const int kKswTwo[] = {16, 24, 28, 32, 12, 14, 8, 11, 10, 4};
         for (int min_kw : {8, 4}) {
             for (int splits = 1; splits <= one.splits; splits *= 2) {
                 if (ks_total % splits) break;

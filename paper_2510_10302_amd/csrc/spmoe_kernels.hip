@@ -96,6 +96,11 @@ __device__ __forceinline__ u32x4 load_global_16(const void* p) {
         (const __attribute__((address_space(1))) void*)p);
 }
 
+template <typename T>
+__device__ __forceinline__ void store_global(T* p, T v) {
+    *reinterpret_cast<__attribute__((address_space(1))) T*>((__attribute__((address_space(1))) void*)p) = v;
+}
+
 // fp32 -> bf16 bits, round to nearest even (finite inputs)
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     uint32_t u = __builtin_bit_cast(uint32_t, f);
@@ -701,11 +706,11 @@ __global__ __launch_bounds__(((KSW > 14 || NTOK == 2) ? 8 : 16) * 64) void exper
             const int st = (NTOK == 2) ? nt : nt * p.nw + sub;     // sub-tile index along N
             if (MODE == MODE_GU) {
                 const float hval = (s0 / (1.f + expf(-s0))) * s1;
-                p.h[(size_t)a_o * N + st * 16 + fi] = (uint16_t)f32_to_bf16_bits(hval);
+                store_global(p.h + (size_t)a_o * N + st * 16 + fi, (uint16_t)f32_to_bf16_bits(hval));
             } else {
                 float* y = p.ypart + ((size_t)s * p.A_tot + a_o) * N + st * 32 + fi;
-                y[0] = s0;
-                y[16] = s1;
+                store_global(y, s0);
+                store_global(y + 16, s1);
             }
         }
         buf ^= 1;

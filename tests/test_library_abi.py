@@ -105,6 +105,24 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
 
 
+def test_bench_finds_the_recorded_counter_traffic():
+    # the roofline block quotes HBM traffic from the committed rocprofv3 summaries: each benchmark shape must have
+    # one that still parses, names the commit it was measured at, and lies between one expert's gate/up bytes and
+    # those of all the layer's experts (+ 2 %): more would mean re-reads were recorded
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    shapes = {"c2_mixtral_8x7b": (4096, 14336, 8, 0), "c4_deepseek_v2_lite": (2048, 1408, 64, 2),
+              "c5_mixtral_8x22b": (6144, 16384, 8, 0)}
+    for name, (d, f, E, shared) in shapes.items():
+        traffic, commit = bench.profiled_traffic(name)
+        assert traffic and commit, name
+        experts = traffic / (2.0 * d * f * 2)
+        assert 1.0 <= experts <= (E + shared) * 1.02, (name, experts)
+    assert bench.profiled_traffic("no_such_workload") == (None, None)
+
+
 def test_no_cpu_fallback_when_the_library_is_missing(sp, monkeypatch):
     from paper_2510_10302_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
